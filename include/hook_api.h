@@ -1,0 +1,171 @@
+/*
+ * hook_api.h - C ABI of the hooked paged-attention library for MI355X (gfx950).
+ *
+ * Two operations, both asynchronous on a caller-supplied HIP stream:
+ *
+ *   hook_attn_probe  causal grouped-query attention forward over a paged KV
+ *                    cache which, for configured heads, also returns the softmax
+ *                    attention mass that chosen query rows place on chosen key
+ *                    spans.  This is the statistic the paper's passive
+ *                    programming obtains by saving q and all k of the configured
+ *                    [layer, head] pairs and recomputing attention afterwards
+ *                    (Section 2.1 worker hook; Section 2.2 analyzer, "recompute
+ *                    selective attentions" and the per-prompt token ranges of
+ *                    `input_range`), here reduced inside the attention kernel so
+ *                    that neither q/k copies nor the probability matrix reach
+ *                    memory.  The attention output is unaffected by probing
+ *                    (Section 1: passive programming keeps generation intact).
+ *
+ *   hook_steer       residual-stream steering, hidden[t,:] += alpha * vec[:] on
+ *                    masked tokens (Section 1, "Model Steering": a steering
+ *                    vector injected into a layer's activations).
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer unless stated otherwise.  The
+ *     caller owns all buffers; the library allocates no device memory, keeps no
+ *     state between calls and never synchronises the stream.  The host reads only
+ *     the scalar fields, so a call is a fixed sequence of kernel launches.
+ *   - Inputs are read-only.  The only writes are `out`, `mass`, `workspace`
+ *     (hook_attn_probe) and `hidden` (hook_steer).
+ *   - Errors are returned as hook_status; nothing is launched or written when a
+ *     call is rejected.  Contents of device arrays (block ids, lengths) cannot be
+ *     checked without a sync: block ids outside [0, num_blocks) are clamped so a
+ *     bad table cannot fault, lengths beyond the table are clamped, and the
+ *     condition is recorded in the workspace (see hook_attn_probe_device_status).
+ *   - One call covers one layer; [layer, head] lists (Section 2, config example)
+ *     are split per layer by the caller.
+ */
+#ifndef HOOK_API_H_
+#define HOOK_API_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HOOK_OK = 0,
+  HOOK_ERR_NULL = 1,         /* a required pointer is null */
+  HOOK_ERR_SHAPE = 2,        /* negative / inconsistent sizes */
+  HOOK_ERR_UNSUPPORTED = 3,  /* dtype, head_dim, block_size or limits not supported */
+  HOOK_ERR_WORKSPACE = 4,    /* workspace missing, misaligned or too small */
+  HOOK_ERR_LAUNCH = 5        /* the HIP runtime refused a launch */
+} hook_status;
+
+typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
+
+#define HOOK_MAX_SPANS 8      /* S: key spans per sequence */
+#define HOOK_MAX_SEL_Q 4096   /* NQ: selected query rows per sequence */
+#define HOOK_BLOCK_SIZE 16    /* tokens per KV-cache block */
+
+/*
+ * Arguments of hook_attn_probe.
+ *
+ * Shapes: Hq = num_q_heads, Hkv = num_kv_heads (Hq % Hkv == 0; q head h reads kv
+ * head h / (Hq / Hkv)), d = head_dim (bf16: 64 or 128; f32: 1..128),
+ * B = block_size (must be 16).
+ *
+ * Sequence i has L_i = seq_lens[i] tokens of context INCLUDING its n_i new
+ * tokens, whose keys/values are already in the cache.  Its query rows are rows
+ * cu_q_lens[i] .. cu_q_lens[i+1]-1 of `q`; chunk-local row t sits at absolute
+ * position pos = L_i - n_i + t and attends to keys 0..pos.  n_i = 0 is allowed
+ * (the sequence is skipped); n_i > L_i is invalid.
+ *
+ * Key j of sequence i, kv head g lives at
+ *   k_cache[block_table[i, j / B], g, j % B, :]      (v_cache likewise).
+ *
+ * Probe: for p in [0, P), head probe_heads[p]; for chunk-local rows t in
+ * [query_sel[i,0], query_sel[i,1]) (at most max_sel_q rows); for span r with
+ * [a, b) = key_spans[i, r, :] in absolute key positions:
+ *   mass[i, p, t - query_sel[i,0], r] = sum of softmax probabilities of row t
+ *                                       over keys max(a,0) .. min(b, pos+1)-1.
+ * Entries with no selected row or an empty span (a >= b after clipping) are 0.
+ * Spans may overlap; they are independent.
+ */
+typedef struct hook_attn_probe_args {
+  /* shapes (host scalars) */
+  int32_t num_seqs;
+  int32_t total_q;             /* rows of q = cu_q_lens[num_seqs] */
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t head_dim;
+  int32_t block_size;
+  int32_t max_blocks_per_seq;  /* row length of block_table; bounds every L_i by max_blocks_per_seq * B */
+  int32_t num_blocks;          /* blocks in k_cache / v_cache */
+  int32_t dtype;               /* hook_dtype of q, k_cache, v_cache, out */
+  float   scale;               /* softmax scale; <= 0 selects 1/sqrt(head_dim) */
+
+  /* inputs (device, borrowed) */
+  const void*    q;            /* [total_q, Hq, d], sequences back to back */
+  const void*    k_cache;      /* [num_blocks, Hkv, B, d] */
+  const void*    v_cache;      /* [num_blocks, Hkv, B, d] */
+  const int32_t* block_table;  /* [num_seqs, max_blocks_per_seq] */
+  const int32_t* seq_lens;     /* [num_seqs] */
+  const int32_t* cu_q_lens;    /* [num_seqs + 1], cu_q_lens[0] = 0 */
+
+  /* probe (num_probe_heads == 0 disables probing; the arrays may then be null) */
+  int32_t        num_probe_heads;  /* P <= Hq */
+  const int32_t* probe_heads;      /* [P] q-head indices, strictly increasing */
+  int32_t        max_sel_q;        /* NQ, 1..HOOK_MAX_SEL_Q */
+  const int32_t* query_sel;        /* [num_seqs, 2] */
+  int32_t        max_spans;        /* S, 1..HOOK_MAX_SPANS */
+  const int32_t* key_spans;        /* [num_seqs, S, 2] */
+
+  /* outputs (device, caller-allocated) */
+  void*  out;                  /* [total_q, Hq, d], dtype as q; rows of skipped sequences untouched */
+  float* mass;                 /* [num_seqs, P, NQ, S] fp32; fully written (zeros where unused) */
+
+  /* scratch (device, caller-allocated, 256-byte aligned) and stream */
+  void*  workspace;
+  size_t workspace_bytes;      /* >= hook_attn_probe_workspace_bytes(args) */
+  void*  stream;               /* hipStream_t; null = the default stream */
+} hook_attn_probe_args;
+
+/*
+ * Bytes of workspace hook_attn_probe needs for these shapes.  Reads only the
+ * scalar shape fields (num_seqs, total_q, head counts, head_dim,
+ * max_blocks_per_seq, max_spans, dtype); returns 0 if they are unsupported.
+ */
+size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* args);
+
+/*
+ * Launches the attention + probe kernels on args->stream and returns without
+ * waiting.  Sequences with one query row take a split-key decode path whose
+ * partial results are merged by a combine kernel; longer chunks take the tiled
+ * prefill path; both may be mixed in one call.  Results are deterministic: the
+ * same inputs give bit-identical `out` and `mass` on every call, for any
+ * physical block permutation, and `out` does not depend on the probe arguments.
+ */
+hook_status hook_attn_probe(const hook_attn_probe_args* args);
+
+/*
+ * Debug aid: copies the device-side status word of the last hook_attn_probe
+ * call that used `workspace` back to the host (this SYNCHRONISES the stream).
+ * *status_bits: bit 0 = some n_i > L_i (sequence skipped), bit 1 = some L_i
+ * exceeded max_blocks_per_seq * B (clamped), bit 2 = negative length.
+ */
+hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits);
+
+/*
+ * hidden[t, :] += alpha * vec[:] for every row t with token_mask[t] != 0,
+ * computed as one fp32 fused multiply-add per element and rounded to the storage
+ * dtype with round-to-nearest-even.  Rows with token_mask[t] == 0 are neither
+ * read nor written.  alpha == 0 returns HOOK_OK without launching, so the buffer
+ * stays bit-identical (signed zeros and NaN payloads included).
+ *   hidden      [num_tokens, hidden_dim], in place, device
+ *   vec         [hidden_dim], dtype of hidden, device
+ *   token_mask  [num_tokens] bytes, device
+ * hidden_dim must be a multiple of 8 (bf16) or 4 (f32).
+ */
+hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t* token_mask,
+                       int32_t num_tokens, int32_t hidden_dim, int32_t dtype, void* stream);
+
+const char* hook_status_string(hook_status status);
+int hook_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HOOK_API_H_ */

@@ -1,0 +1,189 @@
+"""ctypes front end of libhook.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+``include/hook_api.h``; torch is used for device memory and the current stream.
+There is no CPU fallback: loading fails loudly if the library has not been
+built (``python -m paper_2603_06588_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhook.so")
+
+HOOK_OK = 0
+HOOK_BF16, HOOK_F32 = 0, 1
+_DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
+EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_device_status",
+           "hook_steer", "hook_status_string", "hook_version"]
+
+
+class HookAttnProbeArgs(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("total_q", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("max_blocks_per_seq", ctypes.c_int32), ("num_blocks", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("q", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p), ("cu_q_lens", ctypes.c_void_p),
+        ("num_probe_heads", ctypes.c_int32), ("probe_heads", ctypes.c_void_p),
+        ("max_sel_q", ctypes.c_int32), ("query_sel", ctypes.c_void_p),
+        ("max_spans", ctypes.c_int32), ("key_spans", ctypes.c_void_p),
+        ("out", ctypes.c_void_p), ("mass", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+class HookError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {status_string(status)} (hook_status {int(status)})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_06588_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        ap = ctypes.POINTER(HookAttnProbeArgs)
+        lib.hook_attn_probe_workspace_bytes.restype = ctypes.c_size_t
+        lib.hook_attn_probe_workspace_bytes.argtypes = [ap]
+        lib.hook_attn_probe.restype = ctypes.c_int
+        lib.hook_attn_probe.argtypes = [ap]
+        lib.hook_attn_probe_device_status.restype = ctypes.c_int
+        lib.hook_attn_probe_device_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
+                                                      ctypes.POINTER(ctypes.c_int32)]
+        lib.hook_steer.restype = ctypes.c_int
+        lib.hook_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        lib.hook_status_string.restype = ctypes.c_char_p
+        lib.hook_status_string.argtypes = [ctypes.c_int]
+        lib.hook_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().hook_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().hook_version())
+
+
+def _p(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None or t.numel() == 0 else t.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+class AttnProbeCall:
+    """A marshalled ``hook_attn_probe`` call that can be launched repeatedly.
+
+    Holds references to every tensor it points at, the output tensors and the
+    workspace, so relaunching costs one ctypes call and no allocation.
+    """
+
+    def __init__(self, q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
+                 query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0, out=None, mass=None,
+                 workspace=None):
+        lib = load_library()
+        if q.dtype not in _DT:
+            raise HookError(3, "hook_attn_probe (dtype)")
+        dev = q.device
+        self.keep = [q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, query_sel, key_spans]
+        total_q, Hq, d = q.shape
+        num_blocks, Hkv, B, _ = k_cache.shape
+        num_seqs, max_blocks = block_table.shape
+        P = 0 if probe_heads is None else int(probe_heads.numel())
+        a = HookAttnProbeArgs()
+        a.num_seqs, a.total_q, a.num_q_heads, a.num_kv_heads = num_seqs, total_q, Hq, Hkv
+        a.head_dim, a.block_size, a.max_blocks_per_seq, a.num_blocks = d, B, max_blocks, num_blocks
+        a.dtype, a.scale = _DT[q.dtype], float(scale)
+        a.q, a.k_cache, a.v_cache = _p(q), _p(k_cache), _p(v_cache)
+        a.block_table, a.seq_lens, a.cu_q_lens = _p(block_table), _p(seq_lens), _p(cu_q_lens)
+        a.num_probe_heads, a.probe_heads = P, _p(probe_heads)
+        a.max_sel_q, a.query_sel = int(max_sel_q), _p(query_sel)
+        a.max_spans, a.key_spans = int(max_spans), _p(key_spans)
+        self.out = out if out is not None else torch.empty_like(q)
+        self.mass = mass if mass is not None else torch.empty((num_seqs, P, int(max_sel_q), int(max_spans)),
+                                                               dtype=torch.float32, device=dev)
+        a.out, a.mass = _p(self.out), _p(self.mass)
+        need = int(lib.hook_attn_probe_workspace_bytes(ctypes.byref(a)))
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        self.workspace = workspace
+        a.workspace, a.workspace_bytes = _p(workspace), workspace.numel()
+        self.args = a
+        self.workspace_needed = need
+        self._fn = lib.hook_attn_probe
+
+    def launch(self, stream=None) -> None:
+        self.args.stream = _stream_handle(stream)
+        st = self._fn(ctypes.byref(self.args))
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe")
+
+    def device_status(self, stream=None) -> int:
+        bits = ctypes.c_int32(0)
+        st = load_library().hook_attn_probe_device_status(self.args.workspace, _stream_handle(stream),
+                                                          ctypes.byref(bits))
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe_device_status")
+        return int(bits.value)
+
+
+def hook_attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
+                    query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0,
+                    stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(out, mass) of one layer's hooked attention; asynchronous on the current stream."""
+    call = AttnProbeCall(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q,
+                         query_sel, max_spans, key_spans, scale)
+    call.launch(stream)
+    return call.out, call.mass
+
+
+def hook_attn_probe_batch(b, stream=None, probe: bool = True):
+    """Convenience for objects carrying the batch attributes (device tensors)."""
+    return hook_attn_probe(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
+                           b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
+                           b.key_spans, b.scale, stream)
+
+
+def call_from_batch(b, probe: bool = True, **kw) -> AttnProbeCall:
+    return AttnProbeCall(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
+                         b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
+                         b.key_spans, b.scale, **kw)
+
+
+def hook_steer(hidden: torch.Tensor, vec: torch.Tensor, alpha: float, token_mask: torch.Tensor,
+               stream=None) -> torch.Tensor:
+    """In place: hidden[t] += alpha * vec where token_mask[t] != 0.  Returns ``hidden``."""
+    lib = load_library()
+    if hidden.dtype not in _DT or vec.dtype != hidden.dtype or token_mask.dtype != torch.uint8:
+        raise HookError(3, "hook_steer (dtype)")
+    if not (hidden.is_contiguous() and vec.is_contiguous() and token_mask.is_contiguous()):
+        raise HookError(2, "hook_steer (layout)")
+    T, D = hidden.shape
+    if vec.numel() != D or token_mask.numel() != T:
+        raise HookError(2, "hook_steer (shape)")
+    st = lib.hook_steer(_p(hidden), _p(vec), float(alpha), _p(token_mask), T, D, _DT[hidden.dtype],
+                        _stream_handle(stream))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_steer")
+    return hidden

@@ -1,0 +1,167 @@
+// Host side of the C ABI declared in include/hook_api.h: argument checks, workspace
+// carve-up and the fixed launch sequence.  No device memory is allocated here and the
+// stream is never synchronised (except in the explicit debug status call).
+#include "../../include/hook_api.h"
+#include "hook_device.h"
+
+#include <cmath>
+
+namespace {
+
+using namespace hook;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  size_t off_hdr, off_pf, off_dec, off_seq, off_part, total;
+  int pf_cap, dec_cap, hpw, rows_per_wg, hgroups, dec_hp, dec_hgroups;
+};
+
+bool shapes_supported(const hook_attn_probe_args* a) {
+  if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0) return false;
+  if (a->max_blocks_per_seq <= 0 || a->num_blocks <= 0) return false;
+  if (a->num_q_heads % a->num_kv_heads != 0) return false;
+  if (a->block_size != HOOK_BLOCK_SIZE) return false;
+  if (a->dtype != HOOK_BF16 && a->dtype != HOOK_F32) return false;
+  if (a->head_dim != 64 && a->head_dim != 128) return false;
+  if (a->max_blocks_per_seq > (1 << 26)) return false;
+  return true;
+}
+
+Layout make_layout(const hook_attn_probe_args* a) {
+  Layout l{};
+  const int G = a->num_q_heads / a->num_kv_heads;
+  l.hpw = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  l.rows_per_wg = kWaveRows * (4 / l.hpw);
+  l.hgroups = G / l.hpw;
+  l.dec_hp = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  l.dec_hgroups = G / l.dec_hp;
+  if (a->dtype == HOOK_BF16) {
+    l.pf_cap = a->total_q / l.rows_per_wg + a->num_seqs;
+    const long long nd = a->num_seqs < a->total_q ? a->num_seqs : a->total_q;
+    const long long per_seq = ((long long)a->max_blocks_per_seq * kBlock + 255) / 256;
+    long long cap = nd * per_seq;
+    if (cap > (1ll << 30)) cap = 1ll << 30;
+    l.dec_cap = (int)cap;
+  }
+  size_t off = 0;
+  l.off_hdr = off;  off = align_up(off + sizeof(PlanHeader));
+  l.off_pf = off;   off = align_up(off + sizeof(WorkItem) * (size_t)l.pf_cap);
+  l.off_dec = off;  off = align_up(off + sizeof(WorkItem) * (size_t)l.dec_cap);
+  l.off_seq = off;  off = align_up(off + sizeof(int2) * (size_t)(a->num_seqs > 0 ? a->num_seqs : 1));
+  l.off_part = off;
+  off = align_up(off + sizeof(float) * (size_t)l.dec_cap * a->num_q_heads * (a->head_dim + kPartialPad));
+  l.total = off;
+  return l;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* a) {
+  if (!a || !shapes_supported(a)) return 0;
+  return make_layout(a).total;
+}
+
+hook_status hook_attn_probe(const hook_attn_probe_args* a) {
+  if (!a) return HOOK_ERR_NULL;
+  if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
+      a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
+    return HOOK_ERR_SHAPE;
+  if (a->num_q_heads % a->num_kv_heads != 0) return HOOK_ERR_SHAPE;
+  if (!shapes_supported(a)) return HOOK_ERR_UNSUPPORTED;
+  const int P = a->num_probe_heads;
+  if (P < 0 || P > a->num_q_heads) return HOOK_ERR_SHAPE;
+  if (P > 0) {
+    if (a->max_sel_q < 1 || a->max_spans < 1) return HOOK_ERR_SHAPE;
+    if (a->max_sel_q > HOOK_MAX_SEL_Q || a->max_spans > HOOK_MAX_SPANS) return HOOK_ERR_UNSUPPORTED;
+    if (!a->probe_heads || !a->query_sel || !a->key_spans || !a->mass) return HOOK_ERR_NULL;
+  }
+  if (a->num_seqs == 0 || a->total_q == 0) return HOOK_OK;
+  if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
+    return HOOK_ERR_NULL;
+  const Layout l = make_layout(a);
+  if (!a->workspace || a->workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(a->workspace) % kAlign) != 0)
+    return HOOK_ERR_WORKSPACE;
+
+  AttnParams p{};
+  p.num_seqs = a->num_seqs;
+  p.total_q = a->total_q;
+  p.Hq = a->num_q_heads;
+  p.Hkv = a->num_kv_heads;
+  p.G = p.Hq / p.Hkv;
+  p.max_blocks = a->max_blocks_per_seq;
+  p.num_blocks = a->num_blocks;
+  const float scale = a->scale > 0.0f ? a->scale : 1.0f / std::sqrt((float)a->head_dim);
+  p.scale_log2 = scale * 1.44269504088896340736f;
+  p.q = a->q; p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+  p.block_table = a->block_table; p.seq_lens = a->seq_lens; p.cu_q_lens = a->cu_q_lens;
+  p.P = P;
+  p.probe_heads = a->probe_heads;
+  p.NQ = P > 0 ? a->max_sel_q : 0;
+  p.query_sel = a->query_sel;
+  p.S = P > 0 ? a->max_spans : 0;
+  p.key_spans = a->key_spans;
+  p.out = a->out;
+  p.mass = a->mass;
+  char* ws = static_cast<char*>(a->workspace);
+  p.hdr = reinterpret_cast<PlanHeader*>(ws + l.off_hdr);
+  p.pf_items = reinterpret_cast<WorkItem*>(ws + l.off_pf);
+  p.pf_cap = l.pf_cap;
+  p.dec_items = reinterpret_cast<WorkItem*>(ws + l.off_dec);
+  p.dec_cap = l.dec_cap;
+  p.seq_dec = reinterpret_cast<int2*>(ws + l.off_seq);
+  p.partials = reinterpret_cast<float*>(ws + l.off_part);
+  p.hpw = l.hpw; p.rows_per_wg = l.rows_per_wg; p.hgroups = l.hgroups;
+  p.dec_hp = l.dec_hp; p.dec_hgroups = l.dec_hgroups;
+
+  hipStream_t st = static_cast<hipStream_t>(a->stream);
+  if (a->dtype == HOOK_F32) {
+    return launch_attn_f32(p, a->head_dim, st) == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
+  }
+  if (launch_plan(p, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  if (launch_prefill(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  if (launch_decode(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  return HOOK_OK;
+}
+
+hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits) {
+  if (!workspace || !status_bits) return HOOK_ERR_NULL;
+  PlanHeader h{};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&h, workspace, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  *status_bits = h.status;
+  return HOOK_OK;
+}
+
+hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t* token_mask,
+                       int32_t num_tokens, int32_t hidden_dim, int32_t dtype, void* stream) {
+  if (num_tokens < 0 || hidden_dim < 0) return HOOK_ERR_SHAPE;
+  if (dtype != HOOK_BF16 && dtype != HOOK_F32) return HOOK_ERR_UNSUPPORTED;
+  if (hidden_dim % (dtype == HOOK_BF16 ? 8 : 4) != 0) return HOOK_ERR_UNSUPPORTED;
+  if (num_tokens == 0 || hidden_dim == 0) return HOOK_OK;
+  if (!hidden || !vec || !token_mask) return HOOK_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(hidden) | reinterpret_cast<uintptr_t>(vec)) % 16 != 0) return HOOK_ERR_UNSUPPORTED;
+  if (alpha == 0.0f) return HOOK_OK;
+  return launch_steer(hidden, vec, alpha, token_mask, num_tokens, hidden_dim, dtype,
+                      static_cast<hipStream_t>(stream)) == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
+}
+
+const char* hook_status_string(hook_status s) {
+  switch (s) {
+    case HOOK_OK: return "ok";
+    case HOOK_ERR_NULL: return "null pointer";
+    case HOOK_ERR_SHAPE: return "inconsistent shape";
+    case HOOK_ERR_UNSUPPORTED: return "unsupported configuration";
+    case HOOK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HOOK_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+int hook_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,366 @@
+// Split-key decode attention (one query row per sequence) and the kernel that merges the
+// per-chunk partial results.
+//
+// The path is bound by HBM: every live K and V element of a kv head is read exactly once
+// and shared by the HP query heads of its group.  A workgroup owns one (sequence, key chunk,
+// kv head); each of its 4 waves streams a contiguous run of 16-key cache blocks straight
+// from global memory into registers (16-byte loads, one block ahead):
+//   - the K block is the A operand of S^T = K Q^T (16x16x32 bf16 MFMA, keys = M, heads = N),
+//     whose accumulator gives lane (head j, key group kq) the scores of 4 keys;
+//   - every (head, key group) lane runs its own online softmax over the keys it sees, so
+//     the loop has no cross-lane reduction; exponentials are handed to the lanes that hold
+//     the matching V rows with a lane shuffle, and P V is plain fp32 FMAs on V in its
+//     natural layout;
+//   - the key-group streams of a wave, the waves of a workgroup and finally the chunks of a
+//     sequence are merged with the usual (max, sum) weights; probe span sums ride along with
+//     the normaliser in every merge.
+#include "hook_device.h"
+
+namespace hook {
+
+namespace {
+
+template <int D>
+struct DecodeCfg {
+  static constexpr int KSTEPS = D / 32;        // MFMA k-steps
+  static constexpr int CHV = D / 8;            // 16-byte chunks per V row
+  static constexpr int VK = 64 / CHV;          // V key groups per block (lanes / chunks)
+  static constexpr int KPL = kBlock / VK;      // keys per V lane per block (4 or 2)
+  static constexpr int PSTR = D + kPartialPad; // floats per partial record
+};
+
+template <int D, int HP>
+__global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
+  using C = DecodeCfg<D>;
+  __shared__ float red[4][HP][C::PSTR];
+
+  const int bid = blockIdx.x;
+  const int kvh = bid % p.Hkv;
+  const int rest = bid / p.Hkv;
+  const int hg = rest % p.dec_hgroups;
+  const int item = rest / p.dec_hgroups;
+  if (item >= p.hdr->n_decode) return;
+  const WorkItem it = p.dec_items[item];
+  const int seq = it.x, chunk = it.y, L = it.z, qrow = it.w;
+  const int CH = p.hdr->chunk_keys;
+  const int kstart = chunk * CH;
+  const int kend = min(L, kstart + CH);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nblk = (kend - kstart + kBlock - 1) / kBlock;
+  const int bpw = (nblk + 3) / 4;
+  const int b0 = min(w * bpw, nblk), b1 = min(b0 + bpw, nblk);
+  const int head0 = kvh * p.G + hg * HP;
+
+  const __bf16* const qg = static_cast<const __bf16*>(p.q);
+  const __bf16* const kg_ = static_cast<const __bf16*>(p.k_cache);
+  const __bf16* const vg_ = static_cast<const __bf16*>(p.v_cache);
+  const int* const bt = p.block_table + (size_t)seq * p.max_blocks;
+  const size_t blk_stride = (size_t)p.Hkv * kBlock * D;
+  const size_t head_off = (size_t)kvh * kBlock * D;
+
+  // score-lane role: head j = lane % 16 (real if j < HP), key group kq = lane / 16
+  const int j = lane & 15, kq = lane >> 4;
+  // value-lane role: key group vk, 16-byte chunk ch; its keys KPL*vk .. KPL*vk+KPL-1 all
+  // belong to score key group (KPL*vk)/4
+  const int vk = lane / C::CHV, ch = lane % C::CHV;
+  const int src_base = 16 * ((C::KPL * vk) >> 2);     // lane of head 0 in the matching score group
+
+  bf16x8 qf[C::KSTEPS];
+#pragma unroll
+  for (int s = 0; s < C::KSTEPS; ++s) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (j < HP)
+      v = *reinterpret_cast<const uint4*>(qg + ((size_t)qrow * p.Hq + head0 + j) * D + 32 * s + 8 * kq);
+    __builtin_memcpy(&qf[s], &v, 16);
+  }
+
+  // probe set-up: per score lane (its head), spans uniform
+  int sp_a[kMaxSpans], sp_b[kMaxSpans];
+#pragma unroll
+  for (int s = 0; s < kMaxSpans; ++s) { sp_a[s] = 0; sp_b[s] = 0; }
+  bool any_probe = false;
+  bool lane_probe = false;
+  if (p.P > 0) {
+    const int qb = p.query_sel[2 * seq], qe = p.query_sel[2 * seq + 1];
+    any_probe = (qb <= 0 && qe > 0);
+    if (any_probe) {
+      lane_probe = (j < HP) && find_probe_slot(p.probe_heads, p.P, head0 + j) >= 0;
+#pragma unroll
+      for (int s = 0; s < kMaxSpans; ++s)
+        if (s < p.S) {
+          sp_a[s] = max(p.key_spans[((size_t)seq * p.S + s) * 2], 0);
+          sp_b[s] = p.key_spans[((size_t)seq * p.S + s) * 2 + 1];
+        }
+    }
+  }
+
+  float m_run = -INFINITY, l_run = 0.0f;
+  float am[kMaxSpans];
+#pragma unroll
+  for (int s = 0; s < kMaxSpans; ++s) am[s] = 0.0f;
+  float acc[HP][8];
+#pragma unroll
+  for (int h = 0; h < HP; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+  const float c = p.scale_log2;
+
+  uint4 kr[2][C::KSTEPS];
+  uint4 vr[2][C::KPL];
+
+  auto load_block = [&](int b, uint4 (&kd)[C::KSTEPS], uint4 (&vd)[C::KPL]) {
+    const int jb = (kstart >> 4) + b;                   // block index inside the sequence
+    int blk = bt[jb];
+    blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
+    const __bf16* kb = kg_ + (size_t)blk * blk_stride + head_off;
+    const __bf16* vb = vg_ + (size_t)blk * blk_stride + head_off;
+    const int key_k = jb * kBlock + j;                  // this lane's key as a score-lane
+    const bool ok_k = key_k < kend;
+#pragma unroll
+    for (int s = 0; s < C::KSTEPS; ++s) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ok_k) v = *reinterpret_cast<const uint4*>(kb + (size_t)j * D + 32 * s + 8 * kq);
+      kd[s] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < C::KPL; ++i) {
+      const int kl = C::KPL * vk + i;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (jb * kBlock + kl < kend) v = *reinterpret_cast<const uint4*>(vb + (size_t)kl * D + 8 * ch);
+      vd[i] = v;
+    }
+  };
+
+  auto compute_block = [&](int b, const uint4 (&kd)[C::KSTEPS], const uint4 (&vd)[C::KPL]) {
+    const int key0 = kstart + b * kBlock;
+    f32x4 sacc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int s = 0; s < C::KSTEPS; ++s) {
+      bf16x8 a;
+      __builtin_memcpy(&a, &kd[s], 16);
+      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[s], sacc, 0, 0, 0);
+    }
+    // lane (j, kq): sacc[r] = score of head j with key key0 + 4 kq + r
+    float tt[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      tt[r] = sacc[r] * c;
+      if (key0 + 4 * kq + r >= kend) tt[r] = -INFINITY;
+    }
+    const float bm = fmaxf(fmaxf(tt[0], tt[1]), fmaxf(tt[2], tt[3]));
+    const bool upd = bm > m_run + kLazyTau;
+    if (__builtin_amdgcn_ballot_w64(upd) != 0) {
+      const float alpha = upd ? fast_exp2(m_run - bm) : 1.0f;
+      m_run = upd ? bm : m_run;
+      l_run *= alpha;
+#pragma unroll
+      for (int s = 0; s < kMaxSpans; ++s) am[s] *= alpha;
+#pragma unroll
+      for (int h = 0; h < HP; ++h) {
+        const float ah = __shfl(alpha, src_base + h);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] *= ah;
+      }
+    }
+    const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;
+    float pr[4];
+    float psum = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      pr[r] = fast_exp2(tt[r] - m_safe);
+      psum += pr[r];
+    }
+    l_run += psum;
+    if (any_probe) {
+#pragma unroll
+      for (int s = 0; s < kMaxSpans; ++s) {
+        if (s < p.S) {
+          const int a = sp_a[s], bnd = sp_b[s];
+          if (bnd > key0 && a < key0 + kBlock) {
+            float add = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int key = key0 + 4 * kq + r;
+              add += (key >= a && key < bnd) ? pr[r] : 0.0f;
+            }
+            am[s] += lane_probe ? add : 0.0f;
+          }
+        }
+      }
+    }
+    // P V on the value lanes
+#pragma unroll
+    for (int i = 0; i < C::KPL; ++i) {
+      float vf[8];
+      vf[0] = bf16_lo(vd[i].x); vf[1] = bf16_hi(vd[i].x);
+      vf[2] = bf16_lo(vd[i].y); vf[3] = bf16_hi(vd[i].y);
+      vf[4] = bf16_lo(vd[i].z); vf[5] = bf16_hi(vd[i].z);
+      vf[6] = bf16_lo(vd[i].w); vf[7] = bf16_hi(vd[i].w);
+#pragma unroll
+      for (int h = 0; h < HP; ++h) {
+        float ph;
+        if constexpr (C::KPL == 4) {
+          ph = __shfl(pr[i], src_base + h);
+        } else {
+          const float lo = __shfl(pr[i], src_base + h);
+          const float hi = __shfl(pr[2 + i], src_base + h);
+          ph = (vk & 1) ? hi : lo;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(ph, vf[e], acc[h][e]);
+      }
+    }
+  };
+
+  // stream this wave's blocks, one block of loads in flight ahead of the arithmetic
+  if (b0 < b1) load_block(b0, kr[0], vr[0]);
+  for (int b = b0; b < b1; b += 2) {
+    if (b + 1 < b1) load_block(b + 1, kr[1], vr[1]);
+    compute_block(b, kr[0], vr[0]);
+    if (b + 1 < b1) {
+      if (b + 2 < b1) load_block(b + 2, kr[0], vr[0]);
+      compute_block(b + 1, kr[1], vr[1]);
+    }
+  }
+
+  // merge the key-group streams of this wave
+  float m_w = fmaxf(m_run, __shfl_xor(m_run, 16));
+  m_w = fmaxf(m_w, __shfl_xor(m_w, 32));
+  const float wgt = (m_run == -INFINITY) ? 0.0f : fast_exp2(m_run - m_w);
+  float l_w = l_run * wgt;
+  l_w += __shfl_xor(l_w, 16);
+  l_w += __shfl_xor(l_w, 32);
+  float am_w[kMaxSpans];
+#pragma unroll
+  for (int s = 0; s < kMaxSpans; ++s) {
+    float v = am[s] * wgt;
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    am_w[s] = v;
+  }
+#pragma unroll
+  for (int h = 0; h < HP; ++h) {
+    const float wh = __shfl(wgt, src_base + h);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[h][e] * wh;
+      if constexpr (C::VK == 8) v += __shfl_xor(v, 8);
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[h][e] = v;
+    }
+  }
+  // lanes with vk == 0 hold o[h][8 ch + e]; score lanes with kq == 0 hold (m, l, a) of head j
+  if (vk == 0) {
+#pragma unroll
+    for (int h = 0; h < HP; ++h)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[w][h][8 * ch + e] = acc[h][e];
+  }
+  if (kq == 0 && j < HP) {
+    red[w][j][D] = m_w;
+    red[w][j][D + 1] = l_w;
+#pragma unroll
+    for (int s = 0; s < kMaxSpans; ++s) red[w][j][D + 2 + s] = am_w[s];
+  }
+  __syncthreads();
+
+  // merge the 4 waves and write one partial record per head
+  for (int idx = tid; idx < HP * C::PSTR; idx += 256) {
+    const int h = idx / C::PSTR, col = idx % C::PSTR;
+    float mm = fmaxf(fmaxf(red[0][h][D], red[1][h][D]), fmaxf(red[2][h][D], red[3][h][D]));
+    float out;
+    if (col == D) {
+      out = mm;
+    } else if (col < D + 2 + kMaxSpans) {
+      out = 0.0f;
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww) {
+        const float mw = red[ww][h][D];
+        const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - mm);
+        out += e * red[ww][h][col];
+      }
+    } else {
+      out = 0.0f;
+    }
+    p.partials[((size_t)item * p.Hq + head0 + h) * C::PSTR + col] = out;
+  }
+}
+
+// One workgroup per (sequence, 4 q heads): wave = head, lane = output columns.
+template <int D>
+__global__ __launch_bounds__(256) void k_combine(const AttnParams p) {
+  using C = DecodeCfg<D>;
+  const int seq = blockIdx.x;
+  const int2 sd = p.seq_dec[seq];
+  if (sd.y <= 0) return;
+  const int lane = threadIdx.x & 63;
+  const int head = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (head >= p.Hq) return;
+  const float* rec0 = p.partials + ((size_t)sd.x * p.Hq + head) * C::PSTR;
+  const size_t rstride = (size_t)p.Hq * C::PSTR;
+
+  float mstar = -INFINITY;
+  for (int cidx = 0; cidx < sd.y; ++cidx) mstar = fmaxf(mstar, rec0[cidx * rstride + D]);
+  float l = 0.0f;
+  float o[D / 64];
+#pragma unroll
+  for (int e = 0; e < D / 64; ++e) o[e] = 0.0f;
+  float a = 0.0f;  // lane s < S merges span s
+  for (int cidx = 0; cidx < sd.y; ++cidx) {
+    const float* rec = rec0 + cidx * rstride;
+    const float mc = rec[D];
+    const float wgt = (mc == -INFINITY) ? 0.0f : fast_exp2(mc - mstar);
+    l += wgt * rec[D + 1];
+#pragma unroll
+    for (int e = 0; e < D / 64; ++e) o[e] += wgt * rec[lane + 64 * e];
+    if (lane < kMaxSpans) a += wgt * rec[D + 2 + lane];
+  }
+  const float inv = 1.0f / l;
+  const int qrow = p.cu_q_lens[seq];
+  __bf16* og = static_cast<__bf16*>(p.out) + ((size_t)qrow * p.Hq + head) * D;
+#pragma unroll
+  for (int e = 0; e < D / 64; ++e) og[lane + 64 * e] = (__bf16)(o[e] * inv);
+  if (p.P > 0 && lane < p.S) {
+    const int qb = p.query_sel[2 * seq], qe = p.query_sel[2 * seq + 1];
+    if (qb <= 0 && qe > 0) {
+      const int pslot = find_probe_slot(p.probe_heads, p.P, head);
+      if (pslot >= 0) p.mass[(((size_t)seq * p.P + pslot) * p.NQ + 0) * p.S + lane] = a * inv;
+    }
+  }
+}
+
+template <int D, int HP>
+hipError_t launch_decode_dh(const AttnParams& p, hipStream_t st) {
+  const long long grid = (long long)p.dec_cap * p.Hkv * p.dec_hgroups;
+  if (grid <= 0) return hipSuccess;
+  hipLaunchKernelGGL((k_decode<D, HP>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_combine<D>, dim3(p.num_seqs, (p.Hq + 3) / 4), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_decode_d(const AttnParams& p, hipStream_t st) {
+  switch (p.dec_hp) {
+    case 8: return launch_decode_dh<D, 8>(p, st);
+    case 4: return launch_decode_dh<D, 4>(p, st);
+    case 2: return launch_decode_dh<D, 2>(p, st);
+    case 1: return launch_decode_dh<D, 1>(p, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_decode(const AttnParams& p, int D, hipStream_t st) {
+  if (D == 128) return launch_decode_d<128>(p, st);
+  if (D == 64) return launch_decode_d<64>(p, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace hook

@@ -1,0 +1,104 @@
+// Internal declarations shared by the HIP translation units of libhook (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hook {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 16;          // tokens per KV block
+constexpr int kMaxSpans = 8;        // compile-time bound on S
+constexpr int kTileKeys = 64;       // keys per prefill tile
+constexpr int kWaveRows = 32;       // query rows per prefill wave
+constexpr int kPartialPad = 16;     // floats after the D output values of a decode partial: m, l, a[8], pad
+constexpr int kPlanBuckets = 2048;  // counting-sort buckets (tile counts) of the prefill work list
+// A running maximum is only raised when a tile's maximum exceeds it by more than this many
+// powers of two; exponentials then stay below 2^kLazyTau, far inside fp32 range, and the
+// normaliser carries the same reference, so the result is the exact softmax.
+constexpr float kLazyTau = 8.0f;
+
+// Device-side status bits written by the plan kernel.
+enum : int { kStatQGtL = 1, kStatLenClamped = 2, kStatNegative = 4 };
+
+struct PlanHeader {
+  int n_prefill;   // prefill work items (row blocks)
+  int n_decode;    // decode work items (key chunks)
+  int chunk_keys;  // keys per decode work item
+  int status;      // kStat* bits
+  int pad[12];
+};
+
+// One record per work item.  prefill: {seq, first chunk-local row, L, n};
+// decode: {seq, chunk index, L, global q row}.
+typedef int4 WorkItem;
+
+struct AttnParams {
+  int num_seqs, total_q, Hq, Hkv, G, max_blocks, num_blocks;
+  float scale_log2;                 // softmax scale * log2(e)
+  const void* q;
+  const void* k_cache;
+  const void* v_cache;
+  const int* block_table;
+  const int* seq_lens;
+  const int* cu_q_lens;
+  int P;
+  const int* probe_heads;
+  int NQ;
+  const int* query_sel;
+  int S;
+  const int* key_spans;
+  void* out;
+  float* mass;
+  // workspace carve-up
+  PlanHeader* hdr;
+  WorkItem* pf_items;
+  int pf_cap;
+  WorkItem* dec_items;
+  int dec_cap;
+  int2* seq_dec;                    // per sequence {first decode item, number of chunks}
+  float* partials;                  // [dec_cap, Hq, D + kPartialPad]
+  // geometry chosen on the host from G
+  int hpw;                          // q heads per prefill workgroup (4, 2 or 1)
+  int rows_per_wg;                  // 32 * (4 / hpw)
+  int hgroups;                      // G / hpw
+  int dec_hp;                       // q heads per decode workgroup (8, 4, 2 or 1)
+  int dec_hgroups;                  // G / dec_hp
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);  // v_cvt_pk_bf16_f32, round-to-nearest-even
+  uint32_t u;
+  __builtin_memcpy(&u, &b, 4);
+  return u;
+}
+
+// Index of `head` in the strictly increasing list probe_heads[0..P), or -1.
+__device__ __forceinline__ int find_probe_slot(const int* probe_heads, int P, int head) {
+  int slot = -1;
+  for (int i = 0; i < P; ++i)
+    if (probe_heads[i] == head) slot = i;
+  return slot;
+}
+
+// launchers (defined next to their kernels); all return hipGetLastError() after the launch
+hipError_t launch_plan(const AttnParams& p, hipStream_t st);
+hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st);
+hipError_t launch_decode(const AttnParams& p, int D, hipStream_t st);
+hipError_t launch_attn_f32(const AttnParams& p, int D, hipStream_t st);
+hipError_t launch_steer(void* hidden, const void* vec, float alpha, const uint8_t* mask, int T, int D,
+                        int dtype, hipStream_t st);
+
+}  // namespace hook

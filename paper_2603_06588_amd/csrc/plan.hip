@@ -1,0 +1,144 @@
+// Device-side planner: reads the ragged batch description and writes the work lists the
+// attention kernels index with blockIdx.  Keeping this on the device means the host never
+// needs the sequence lengths, so a call is a fixed launch sequence.
+//
+//   prefill items  one per (sequence with n_i >= 2, block of rows_per_wg query rows), ordered
+//                  by decreasing number of key tiles (longest first) with a counting sort;
+//   decode items   one per (sequence with n_i == 1, chunk of chunk_keys keys); the chunk size
+//                  is picked so that the decode grid has enough workgroups to fill the chip.
+// The same launch zero-fills `mass`.
+#include "hook_device.h"
+
+namespace hook {
+
+namespace {
+
+constexpr int kPlanThreads = 1024;
+
+struct SeqInfo { int L, n, row0, kind; };  // kind: 0 skip, 1 prefill, 2 decode
+
+__device__ __forceinline__ SeqInfo read_seq(const AttnParams& p, int i, int* status) {
+  SeqInfo s;
+  s.L = p.seq_lens[i];
+  s.row0 = p.cu_q_lens[i];
+  s.n = p.cu_q_lens[i + 1] - s.row0;
+  s.kind = 0;
+  const int max_ctx = p.max_blocks * kBlock;
+  if (s.L < 0 || s.n < 0) { *status |= kStatNegative; return s; }
+  if (s.L > max_ctx) { *status |= kStatLenClamped; s.L = max_ctx; }
+  if (s.n > s.L) { *status |= kStatQGtL; return s; }
+  if (s.row0 < 0 || s.row0 + s.n > p.total_q) { *status |= kStatNegative; return s; }
+  if (s.n == 0) return s;
+  s.kind = (s.n == 1) ? 2 : 1;
+  return s;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
+  const int tid = threadIdx.x;
+  // every block helps clearing mass
+  const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
+  for (size_t i = (size_t)blockIdx.x * kPlanThreads + tid; i < nmass; i += (size_t)gridDim.x * kPlanThreads)
+    p.mass[i] = 0.0f;
+  if (blockIdx.x != 0) return;
+
+  __shared__ int hist[kPlanBuckets];
+  __shared__ int scan[kPlanBuckets];
+  __shared__ int sh_cnt[4];     // decode chunk counts for 256 / 512 / 1024 keys, status
+  __shared__ int sh_dec_next;
+
+  for (int b = tid; b < kPlanBuckets; b += kPlanThreads) hist[b] = 0;
+  if (tid < 4) sh_cnt[tid] = 0;
+  if (tid == 0) sh_dec_next = 0;
+  __syncthreads();
+
+  // pass 1: histogram of prefill items by tile count, decode chunk counts per candidate size
+  int status = 0;
+  int c256 = 0, c512 = 0, c1024 = 0;
+  for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
+    const SeqInfo s = read_seq(p, i, &status);
+    if (s.kind == 1) {
+      for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
+        const int last = min(r0 + p.rows_per_wg, s.n) - 1;
+        const int tiles = (s.L - s.n + last) / kTileKeys + 1;
+        atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+      }
+    } else if (s.kind == 2) {
+      c256 += (s.L + 255) / 256;
+      c512 += (s.L + 511) / 512;
+      c1024 += (s.L + 1023) / 1024;
+    }
+  }
+  if (c256) { atomicAdd(&sh_cnt[0], c256); atomicAdd(&sh_cnt[1], c512); atomicAdd(&sh_cnt[2], c1024); }
+  if (status) atomicOr(&sh_cnt[3], status);
+  __syncthreads();
+
+  // descending exclusive offsets: scan[b] = number of items in buckets above b
+  for (int b = tid; b < kPlanBuckets; b += kPlanThreads) scan[b] = hist[kPlanBuckets - 1 - b];
+  __syncthreads();
+  for (int off = 1; off < kPlanBuckets; off <<= 1) {
+    int v[kPlanBuckets / kPlanThreads];
+#pragma unroll
+    for (int k = 0; k < kPlanBuckets / kPlanThreads; ++k) {
+      const int b = tid + k * kPlanThreads;
+      v[k] = scan[b] + (b >= off ? scan[b - off] : 0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kPlanBuckets / kPlanThreads; ++k) scan[tid + k * kPlanThreads] = v[k];
+    __syncthreads();
+  }
+  // scan is now inclusive over reversed buckets; turn bucket b's slot into its running cursor
+  const int n_prefill = scan[kPlanBuckets - 1];
+  for (int b = tid; b < kPlanBuckets; b += kPlanThreads) {
+    const int rb = kPlanBuckets - 1 - b;  // position of bucket b in the reversed order
+    hist[b] = scan[rb] - hist[b];         // exclusive start (hist[b] still holds the count)
+  }
+  // chunk size: the largest candidate that still yields >= 4096 decode workgroups, else 256
+  const int wg_per_item = p.Hkv * p.dec_hgroups;
+  int chunk = 256;
+  if ((long long)sh_cnt[2] * wg_per_item >= 4096) chunk = 1024;
+  else if ((long long)sh_cnt[1] * wg_per_item >= 4096) chunk = 512;
+  __syncthreads();
+
+  // pass 2: scatter
+  for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
+    int dummy = 0;
+    const SeqInfo s = read_seq(p, i, &dummy);
+    int2 sd = make_int2(0, 0);
+    if (s.kind == 1) {
+      for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
+        const int last = min(r0 + p.rows_per_wg, s.n) - 1;
+        const int tiles = (s.L - s.n + last) / kTileKeys + 1;
+        const int slot = atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+        if (slot < p.pf_cap) p.pf_items[slot] = make_int4(i, r0, s.L, s.n);
+      }
+    } else if (s.kind == 2) {
+      const int nch = (s.L + chunk - 1) / chunk;
+      const int base = atomicAdd(&sh_dec_next, nch);
+      if (base + nch <= p.dec_cap) {
+        sd = make_int2(base, nch);
+        for (int c = 0; c < nch; ++c) p.dec_items[base + c] = make_int4(i, c, s.L, s.row0);
+      }
+    }
+    p.seq_dec[i] = sd;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    p.hdr->n_prefill = min(n_prefill, p.pf_cap);
+    p.hdr->n_decode = min(sh_dec_next, p.dec_cap);
+    p.hdr->chunk_keys = chunk;
+    p.hdr->status = sh_cnt[3];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_plan(const AttnParams& p, hipStream_t st) {
+  const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
+  int blocks = 1 + (int)((nmass + 8 * kPlanThreads - 1) / (8 * kPlanThreads));
+  if (blocks > 64) blocks = 64;
+  hipLaunchKernelGGL(k_plan, dim3(blocks), dim3(kPlanThreads), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace hook

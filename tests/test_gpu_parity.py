@@ -1,0 +1,187 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI (needs an MI355X)."""
+import pytest
+import torch
+
+from paper_2603_06588_amd import workloads as W
+from helpers import bits, compare_with_oracle, run_hip
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _check(b_cpu, rows=None, label=None):
+    print(f"[case] {label or b_cpu.name} seqs={b_cpu.num_seqs} total_q={b_cpu.total_q}", flush=True)
+    b = b_cpu.to(DEV)
+    out, mass = run_hip(b)
+    res = compare_with_oracle(b_cpu, out, mass, rows=rows, label=label or b_cpu.name)
+    print(f"       {res}", flush=True)
+    return b, out, mass
+
+
+# ---- small element-by-element cases: several tiles, ragged tails, both paths ----
+
+SMALL = [
+    # seed, seq_lens, q_lens, Hq, Hkv, d, std
+    (101, [200], [200], 8, 2, 128, 1.0),                       # prefill, 4 tiles, G=4
+    (102, [77, 130, 65, 64], [77, 130, 65, 64], 8, 2, 128, 1.0),  # ragged, tile-edge lengths
+    (103, [300, 150], [45, 150], 8, 2, 128, 1.0),               # chunk on prior context
+    (104, [500, 33, 257, 1025], [1, 1, 1, 1], 8, 2, 128, 1.0),  # decode, ragged contexts
+    (105, [700, 90, 1, 260], [1, 90, 1, 3], 8, 2, 128, 1.0),    # mixed decode + prefill + tiny chunk
+    (106, [190, 64], [190, 64], 8, 1, 128, 1.0),                # G=8
+    (107, [150, 40], [150, 40], 6, 2, 128, 1.0),                # G=3 -> one head per wave
+    (108, [150, 40], [150, 40], 4, 2, 128, 1.0),                # G=2
+    (109, [140, 70], [140, 70], 4, 4, 128, 1.0),                # G=1
+    (110, [210, 90, 300], [210, 1, 1], 8, 2, 64, 1.0),          # d=64, both paths
+    (111, [129, 512], [129, 1], 16, 2, 128, 0.09),              # near-uniform attention
+    (112, [40, 0, 25], [40, 0, 25], 8, 2, 128, 1.0),            # empty sequence in the middle
+    (113, [2100], [1], 8, 8, 128, 1.0),                         # long single decode, G=1
+    (114, [330, 330], [1, 1], 6, 2, 64, 1.0),                   # decode, G=3, d=64
+]
+
+
+@pytest.mark.parametrize("seed,lens,qlens,Hq,Hkv,d,std", SMALL)
+def test_small_batches(seed, lens, qlens, Hq, Hkv, d, std):
+    b = W.random_batch(seed, lens, qlens, Hq, Hkv, d, torch.bfloat16, std=std, num_probe_heads=min(5, Hq),
+                       max_sel_q=6, max_spans=3)
+    _check(b, label=f"small_{seed}")
+
+
+def test_many_spans_and_rows():
+    b = W.random_batch(120, [260, 100], [260, 100], 8, 2, 128, torch.bfloat16, num_probe_heads=8, max_sel_q=70,
+                       max_spans=8)
+    b.query_sel[0, 0], b.query_sel[0, 1] = 180, 250   # spans two row blocks and a tile edge
+    _check(b, label="many_spans")
+
+
+def test_fp32_small():
+    b = W.random_batch(130, [100, 37, 64], [100, 5, 1], 8, 2, 64, torch.float32, num_probe_heads=4, max_sel_q=4,
+                       max_spans=2)
+    _check(b, label="fp32_small")
+    b = W.random_batch(131, [70, 20], [70, 1], 4, 2, 128, torch.float32, num_probe_heads=4, max_sel_q=4, max_spans=2)
+    _check(b, label="fp32_small_d128")
+
+
+# ---- invariants that must hold bit for bit ----
+
+@pytest.mark.parametrize("lens,qlens", [([333, 150], [333, 150]), ([900, 450, 64], [1, 1, 1]), ([400, 200], [1, 200])])
+def test_paging_permutation_is_bit_exact(lens, qlens):
+    kw = dict(num_q_heads=8, num_kv_heads=2, head_dim=128, dtype=torch.bfloat16, num_probe_heads=4)
+    shuf = W.random_batch(140, lens, qlens, shuffle=True, poison=True, **kw)
+    ident = W.random_batch(140, lens, qlens, shuffle=False, poison=False, **kw)
+    ident.q = shuf.q.clone()
+    ident.query_sel, ident.key_spans, ident.probe_heads = shuf.query_sel, shuf.key_spans, shuf.probe_heads
+    for i, L in enumerate(lens):
+        for jb in range((L + 15) // 16):
+            ident.k_cache[int(ident.block_table[i, jb])] = shuf.k_cache[int(shuf.block_table[i, jb])]
+            ident.v_cache[int(ident.block_table[i, jb])] = shuf.v_cache[int(shuf.block_table[i, jb])]
+    o1, m1 = run_hip(shuf.to(DEV))
+    o2, m2 = run_hip(ident.to(DEV))
+    assert torch.equal(bits(o1), bits(o2))
+    assert torch.equal(bits(m1), bits(m2))
+    assert torch.isfinite(o1.float()).all()
+
+
+def test_two_runs_bit_identical_and_probe_does_not_change_out():
+    b_cpu = W.random_batch(150, [520, 300, 800, 64], [520, 1, 1, 64], 8, 2, 128, torch.bfloat16, num_probe_heads=6,
+                           max_sel_q=8, max_spans=4)
+    b = b_cpu.to(DEV)
+    o1, m1 = run_hip(b)
+    o2, m2 = run_hip(b)
+    assert torch.equal(bits(o1), bits(o2)) and torch.equal(bits(m1), bits(m2))
+    o3, m3 = run_hip(b, probe=False)
+    assert torch.equal(bits(o1), bits(o3))
+    assert m3.numel() == 0
+
+
+def test_mass_is_fully_written():
+    from paper_2603_06588_amd import binding
+    b_cpu = W.random_batch(151, [100, 50, 10], [100, 1, 0], 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=5,
+                           max_spans=3)
+    b = b_cpu.to(DEV)
+    mass = torch.full((3, 3, 5, 3), float("nan"), dtype=torch.float32, device=DEV)
+    call = binding.call_from_batch(b, mass=mass)
+    call.launch()
+    torch.cuda.synchronize()
+    assert torch.isfinite(mass).all()
+    compare_with_oracle(b_cpu, call.out, mass, label="mass_written")
+    assert call.device_status() == 0
+
+
+def test_uniform_attention_closed_form_on_gpu():
+    b_cpu = W.random_batch(152, [300, 700], [300, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=8, max_sel_q=4,
+                           max_spans=3, wild_spans=False)
+    b_cpu.q.zero_()
+    b = b_cpu.to(DEV)
+    out, mass = run_hip(b)
+    qs, ks = b_cpu.query_sel.tolist(), b_cpu.key_spans.tolist()
+    for i, (L, n) in enumerate([(300, 300), (700, 1)]):
+        for tt in range(qs[i][1] - qs[i][0]):
+            pos = L - n + qs[i][0] + tt
+            for r in range(3):
+                a, e = ks[i][r]
+                want = max(0, min(e, pos + 1) - max(a, 0)) / (pos + 1)
+                assert (mass[i, :, tt, r].cpu() - want).abs().max() < 1e-5
+
+
+# ---- the named workloads ----
+
+def test_c1_tiny_prefill_fp32():
+    b, s = W.c1_tiny_prefill()
+    _check(b, label="c1")
+
+
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c2_c3_c5_shrunk(peaked):
+    _check(W.c2_prefill_8b(peaked=peaked, shrink=4), label=f"c2_shrink4_peaked{peaked}")
+    _check(W.c3_decode_8b(peaked=peaked, shrink=8), label=f"c3_shrink8_peaked{peaked}")
+    b5, _ = W.c5_mixed(peaked=peaked, shrink=8)
+    _check(b5, label=f"c5_shrink8_peaked{peaked}")
+    b5p, _ = W.c5_mixed(peaked=peaked, shrink=8, prior_context=True)
+    _check(b5p, label=f"c5_prior_shrink8_peaked{peaked}")
+    _check(W.c4_long_prefill_70b(peaked=peaked, shrink=16), label=f"c4_shrink16_peaked{peaked}")
+
+
+def _sample_rows(b, per_seq: int, seed: int):
+    """Probed rows plus tile-boundary and seeded-random rows of every sequence."""
+    gen = torch.Generator().manual_seed(seed)
+    cu = b.cu_q_lens.tolist()
+    qs = b.query_sel.tolist()
+    rows = set()
+    for i in range(b.num_seqs):
+        n = cu[i + 1] - cu[i]
+        if n == 0:
+            continue
+        for t in range(max(qs[i][0], 0), min(qs[i][1], n)):
+            rows.add(cu[i] + t)
+        fixed = [0, 1, 31, 32, 63, 64, 65, 127, 128, n // 2, n - 65, n - 64, n - 33, n - 32, n - 1]
+        rnd = torch.randint(0, n, (per_seq,), generator=gen).tolist()
+        for t in fixed + rnd:
+            if 0 <= t < n:
+                rows.add(cu[i] + t)
+    return sorted(rows)
+
+
+def test_c2_full_size_sampled_rows():
+    b = W.c2_prefill_8b()
+    _check(b, rows=_sample_rows(b, 24, 1), label="c2_full")
+
+
+def test_c2_full_size_peaked_sampled_rows():
+    b = W.c2_prefill_8b(peaked=True)
+    _check(b, rows=_sample_rows(b, 12, 2), label="c2_full_peaked")
+
+
+def test_c3_full_size():
+    b = W.c3_decode_8b(device="cpu")
+    _check(b, label="c3_full")
+
+
+def test_c4_full_size_sampled_rows():
+    b = W.c4_long_prefill_70b()
+    _check(b, rows=_sample_rows(b, 40, 3), label="c4_full")
+
+
+def test_c5_full_size_sampled_rows():
+    b, s = W.c5_mixed()
+    _check(b, rows=_sample_rows(b, 24, 4), label="c5_full")

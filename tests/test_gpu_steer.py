@@ -1,0 +1,75 @@
+"""hook_steer against the CPU oracle (needs an MI355X)."""
+import pytest
+import torch
+
+import oracle
+from paper_2603_06588_amd import workloads as W
+from helpers import bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _ulp_diff(a: torch.Tensor, b: torch.Tensor) -> int:
+    """Largest distance in units of the last place between same-dtype tensors (finite values)."""
+    ia, ib = bits(a).to(torch.int64), bits(b).to(torch.int64)
+    if a.dtype == torch.bfloat16:
+        ia, ib = ia & 0xFFFF, ib & 0xFFFF
+        sign = 0x8000
+    else:
+        ia, ib = ia & 0xFFFFFFFF, ib & 0xFFFFFFFF
+        sign = 0x80000000
+    # map sign-magnitude to a monotone integer line
+    ma = torch.where(ia >= sign, sign - ia, ia)
+    mb = torch.where(ib >= sign, sign - ib, ib)
+    return int((ma - mb).abs().max())
+
+
+def _run(s):
+    from paper_2603_06588_amd import binding
+    d = s.to(DEV)
+    binding.hook_steer(d.hidden, d.vec, d.alpha, d.token_mask)
+    torch.cuda.synchronize()
+    return d.hidden.cpu()
+
+
+@pytest.mark.parametrize("dtype,T,D", [(torch.bfloat16, 300, 4096), (torch.bfloat16, 17, 520), (torch.float32, 65, 512),
+                                       (torch.float32, 9, 36)])
+def test_steer_matches_oracle_within_one_ulp(dtype, T, D):
+    s = W.steer_batch(200 + T, T, D, dtype, alpha=3.25, mask_frac=0.6)
+    want = oracle.steer_batch(s)
+    got = _run(s)
+    keep = s.token_mask == 0
+    assert torch.equal(bits(got)[keep], bits(s.hidden)[keep])      # unmasked rows bit-identical
+    assert _ulp_diff(got, want) <= 1
+
+
+def test_steer_alpha_zero_and_empty_mask_are_bit_identical():
+    s = W.steer_batch(210, 40, 256, torch.bfloat16, alpha=0.0)
+    s.hidden[3, 5] = float("nan")
+    s.hidden[4, 6] = -0.0
+    assert torch.equal(bits(_run(s)), bits(s.hidden))
+    s.alpha = 5.0
+    s.token_mask.zero_()
+    assert torch.equal(bits(_run(s)), bits(s.hidden))
+
+
+def test_steer_cancels_row_exactly():
+    s = W.steer_batch(211, 12, 128, torch.float32, alpha=1.0)
+    s.token_mask.zero_()
+    s.token_mask[7] = 1
+    s.vec = -s.hidden[7].clone()
+    got = _run(s)
+    assert (got[7] == 0).all()
+
+
+def test_c1_and_c5_steer():
+    _, s1 = W.c1_tiny_prefill()
+    assert _ulp_diff(_run(s1), oracle.steer_batch(s1)) <= 1
+    _, s5 = W.c5_mixed()
+    got, want = _run(s5), oracle.steer_batch(s5)
+    assert _ulp_diff(got, want) <= 1
+    # the 192 padding rows and the 64 decode rows are untouched
+    keep = s5.token_mask == 0
+    assert int(keep.sum()) == 64 + 192
+    assert torch.equal(bits(got)[keep], bits(s5.hidden)[keep])

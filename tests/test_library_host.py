@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, and rejects malformed arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2603_06588_amd import binding as b, build
+    if build.lib_is_stale():
+        build.build_lib()
+    return b
+
+
+def test_exports_every_declared_symbol(binding):
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    declared = set(re.findall(r"\b(hook_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = binding.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert binding.version() >= 1
+    assert binding.status_string(0) == "ok"
+
+
+def test_args_struct_matches_header_field_order(binding):
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    body = header[header.index("typedef struct hook_attn_probe_args {"):header.index("} hook_attn_probe_args;")]
+    fields = re.findall(r"^\s*(?:const\s+)?[a-z0-9_]+\*?\s+\*?\s*([a-z_]+);", body, flags=re.M)
+    assert fields == [f[0] for f in binding.HookAttnProbeArgs._fields_]
+
+
+def _args(binding, **kw):
+    a = binding.HookAttnProbeArgs()
+    base = dict(num_seqs=2, total_q=10, num_q_heads=8, num_kv_heads=2, head_dim=128, block_size=16,
+                max_blocks_per_seq=4, num_blocks=16, dtype=0, scale=0.0)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_rejects_bad_arguments_before_launch(binding):
+    lib = binding.load_library()
+    call = lambda a: lib.hook_attn_probe(ctypes.byref(a))
+    assert lib.hook_attn_probe(None) == 1
+    assert call(_args(binding, num_q_heads=6, num_kv_heads=4)) == 2       # Hq % Hkv != 0
+    assert call(_args(binding, head_dim=96)) == 3
+    assert call(_args(binding, block_size=32)) == 3
+    assert call(_args(binding, dtype=7)) == 3
+    assert call(_args(binding, num_seqs=-1)) == 2
+    assert call(_args(binding)) == 1                                      # null tensors
+    a = _args(binding, num_probe_heads=2, max_sel_q=1, max_spans=9)
+    assert call(a) == 3                                                   # too many spans
+    a = _args(binding, num_probe_heads=2, max_sel_q=1, max_spans=1)
+    assert call(a) == 1                                                   # probe arrays null
+    a = _args(binding, num_probe_heads=9)
+    assert call(a) == 2                                                   # more probe heads than heads
+    # everything non-null but no workspace
+    a = _args(binding)
+    for f in ("q", "k_cache", "v_cache", "block_table", "seq_lens", "cu_q_lens", "out"):
+        setattr(a, f, 4096)
+    assert call(a) == 4
+    a.workspace, a.workspace_bytes = 4096 + 8, 1 << 30                    # misaligned
+    assert call(a) == 4
+    assert lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, head_dim=96))) == 0
+    assert lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding))) > 0
+    # empty batch is a no-op
+    assert call(_args(binding, num_seqs=0, total_q=0)) == 0
+
+
+def test_steer_argument_checks(binding):
+    lib = binding.load_library()
+    assert lib.hook_steer(None, None, 1.0, None, 4, 64, 0, None) == 1
+    assert lib.hook_steer(4096, 4096, 1.0, 4096, 4, 60, 0, None) == 3     # not a multiple of 8
+    assert lib.hook_steer(4096, 4096, 1.0, 4096, 4, 64, 5, None) == 3
+    assert lib.hook_steer(4096, 4096, 1.0, 4096, -1, 64, 0, None) == 2
+    assert lib.hook_steer(4096, 4096, 0.0, 4096, 4, 64, 0, None) == 0     # alpha = 0: nothing launched
+    assert lib.hook_steer(None, None, 1.0, None, 0, 64, 0, None) == 0
+
+
+def test_workspace_size_grows_with_decode_capacity(binding):
+    lib = binding.load_library()
+    small = lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, num_seqs=4, total_q=4, max_blocks_per_seq=64)))
+    big = lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, num_seqs=4, total_q=4, max_blocks_per_seq=512)))
+    assert big > small > 0
