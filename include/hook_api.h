@@ -64,7 +64,7 @@ typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
  * Arguments of hook_attn_probe.
  *
  * Shapes: Hq = num_q_heads, Hkv = num_kv_heads (Hq % Hkv == 0; q head h reads kv
- * head h / (Hq / Hkv)), d = head_dim (bf16: 64 or 128; f32: 1..128),
+ * head h / (Hq / Hkv)), d = head_dim (64 or 128, both dtypes),
  * B = block_size (must be 16).
  *
  * Sequence i has L_i = seq_lens[i] tokens of context INCLUDING its n_i new
@@ -139,6 +139,15 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* args);
  * physical block permutation, and `out` does not depend on the probe arguments.
  */
 hook_status hook_attn_probe(const hook_attn_probe_args* args);
+
+/*
+ * Profiling aid: the same launches as hook_attn_probe, bracketed by HIP events on
+ * args->stream, then WAITS for them.  kernel_ms (HOST pointer, 4 floats) receives the
+ * durations in milliseconds of the plan, prefill, decode and combine kernels (fp32
+ * inputs: the single attention kernel in kernel_ms[0], the rest 0).  Creates and
+ * destroys HIP events; not for graph capture.
+ */
+hook_status hook_attn_probe_timed(const hook_attn_probe_args* args, float* kernel_ms);
 
 /*
  * Debug aid: copies the device-side status word of the last hook_attn_probe

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libhook.so")
 HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
-EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_device_status",
+EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
+           "hook_attn_probe_device_status",
            "hook_steer", "hook_status_string", "hook_version"]
 
 
@@ -61,6 +62,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_attn_probe_workspace_bytes.argtypes = [ap]
         lib.hook_attn_probe.restype = ctypes.c_int
         lib.hook_attn_probe.argtypes = [ap]
+        lib.hook_attn_probe_timed.restype = ctypes.c_int
+        lib.hook_attn_probe_timed.argtypes = [ap, ctypes.POINTER(ctypes.c_float)]
         lib.hook_attn_probe_device_status.restype = ctypes.c_int
         lib.hook_attn_probe_device_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
                                                       ctypes.POINTER(ctypes.c_int32)]
@@ -138,6 +141,15 @@ class AttnProbeCall:
         st = self._fn(ctypes.byref(self.args))
         if st != HOOK_OK:
             raise HookError(st, "hook_attn_probe")
+
+    def launch_timed(self, stream=None):
+        """Launch, wait, and return the (plan, prefill, decode, combine) kernel times in ms."""
+        self.args.stream = _stream_handle(stream)
+        ms = (ctypes.c_float * 4)()
+        st = load_library().hook_attn_probe_timed(ctypes.byref(self.args), ms)
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe_timed")
+        return [float(x) for x in ms]
 
     def device_status(self, stream=None) -> int:
         bits = ctypes.c_int32(0)

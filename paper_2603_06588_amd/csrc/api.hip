@@ -65,7 +65,9 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* a) {
   return make_layout(a).total;
 }
 
-hook_status hook_attn_probe(const hook_attn_probe_args* a) {
+// Validates, carves the workspace and launches.  With `ev` (5 events) the launches are
+// bracketed by event records so a profiling caller can read per-kernel durations.
+static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev) {
   if (!a) return HOOK_ERR_NULL;
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
@@ -118,13 +120,39 @@ hook_status hook_attn_probe(const hook_attn_probe_args* a) {
   p.dec_hp = l.dec_hp; p.dec_hgroups = l.dec_hgroups;
 
   hipStream_t st = static_cast<hipStream_t>(a->stream);
+  auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
+  if (!mark(0)) return HOOK_ERR_LAUNCH;
   if (a->dtype == HOOK_F32) {
-    return launch_attn_f32(p, a->head_dim, st) == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
+    if (launch_attn_f32(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+    for (int i = 1; i < 5; ++i)
+      if (!mark(i)) return HOOK_ERR_LAUNCH;
+    return HOOK_OK;
   }
-  if (launch_plan(p, st) != hipSuccess) return HOOK_ERR_LAUNCH;
-  if (launch_prefill(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
-  if (launch_decode(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
+  if (launch_plan(p, st) != hipSuccess || !mark(1)) return HOOK_ERR_LAUNCH;
+  if (launch_prefill(p, a->head_dim, st) != hipSuccess || !mark(2)) return HOOK_ERR_LAUNCH;
+  if (launch_decode(p, a->head_dim, st) != hipSuccess || !mark(3)) return HOOK_ERR_LAUNCH;
+  if (launch_combine(p, a->head_dim, st) != hipSuccess || !mark(4)) return HOOK_ERR_LAUNCH;
   return HOOK_OK;
+}
+
+hook_status hook_attn_probe(const hook_attn_probe_args* a) { return run_attn_probe(a, nullptr); }
+
+hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_ms) {
+  if (!kernel_ms) return HOOK_ERR_NULL;
+  hipEvent_t ev[5];
+  int made = 0;
+  for (; made < 5; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  hook_status rc = made == 5 ? run_attn_probe(a, ev) : HOOK_ERR_LAUNCH;
+  if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
+    if (hipEventSynchronize(ev[4]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
+    for (int i = 0; i < 4 && rc == HOOK_OK; ++i)
+      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
+  } else {
+    for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits) {

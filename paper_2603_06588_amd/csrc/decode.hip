@@ -338,9 +338,6 @@ hipError_t launch_decode_dh(const AttnParams& p, hipStream_t st) {
   const long long grid = (long long)p.dec_cap * p.Hkv * p.dec_hgroups;
   if (grid <= 0) return hipSuccess;
   hipLaunchKernelGGL((k_decode<D, HP>), dim3((unsigned)grid), dim3(256), 0, st, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_combine<D>, dim3(p.num_seqs, (p.Hq + 3) / 4), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 
@@ -361,6 +358,15 @@ hipError_t launch_decode(const AttnParams& p, int D, hipStream_t st) {
   if (D == 128) return launch_decode_d<128>(p, st);
   if (D == 64) return launch_decode_d<64>(p, st);
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_combine(const AttnParams& p, int D, hipStream_t st) {
+  if (p.dec_cap <= 0 || p.num_seqs <= 0) return hipSuccess;
+  const dim3 grid((unsigned)p.num_seqs, (unsigned)((p.Hq + 3) / 4));
+  if (D == 128) hipLaunchKernelGGL(k_combine<128>, grid, dim3(256), 0, st, p);
+  else if (D == 64) hipLaunchKernelGGL(k_combine<64>, grid, dim3(256), 0, st, p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 }  // namespace hook
