@@ -136,6 +136,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5"],
+                    help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -153,6 +155,25 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     only = set(x for x in args.only.split(",") if x) or {"c2", "c3", "c4", "c5"}
+    if args.profile_workload:
+        wl = args.profile_workload
+        steer = None
+        if wl == "c2":
+            b = W.c2_prefill_8b(device=dev)
+        elif wl == "c3":
+            b = W.c3_decode_8b(device=dev)
+        elif wl == "c4":
+            b = W.c4_long_prefill_70b(device=dev)
+        else:
+            b, steer = W.c5_mixed(device=dev)
+        call = binding.call_from_batch(b)
+        for _ in range(args.warmup + args.steps):
+            call.launch()
+            if steer is not None:
+                binding.hook_steer(steer.hidden, steer.vec, steer.alpha, steer.token_mask)
+        torch.cuda.synchronize()
+        print(f"profiled {wl}: {args.warmup + args.steps} launches", file=sys.stderr)
+        return 0
     K, Wm = args.steps, args.warmup
     extra = {}
 

@@ -96,6 +96,7 @@ __device__ __forceinline__ int find_probe_slot(const int* probe_heads, int P, in
 // launchers (defined next to their kernels); all return hipGetLastError() after the launch
 hipError_t launch_plan(const AttnParams& p, hipStream_t st);
 hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st);
+hipError_t launch_prefill128(const AttnParams& p, hipStream_t st);
 hipError_t launch_decode(const AttnParams& p, int D, hipStream_t st);
 hipError_t launch_combine(const AttnParams& p, int D, hipStream_t st);
 hipError_t launch_attn_f32(const AttnParams& p, int D, hipStream_t st);

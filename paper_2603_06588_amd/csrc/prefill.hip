@@ -352,7 +352,7 @@ hipError_t launch_prefill_d(const AttnParams& p, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st) {
-  if (D == 128) return launch_prefill_d<128>(p, st);
+  if (D == 128) return launch_prefill128(p, st);
   if (D == 64) return launch_prefill_d<64>(p, st);
   return hipErrorInvalidValue;
 }
