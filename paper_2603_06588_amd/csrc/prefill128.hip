@@ -45,45 +45,146 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// 16-byte direct-to-LDS load: lane i's data lands at lds + 16 * i.  Written as assembly so
+// that its completion is tracked only by the explicit vmcnt wait at the top of each
+// iteration; the compiler would otherwise make every later LDS read wait for the load.
+__device__ __forceinline__ void dma16(const void* base, unsigned voff, const void* lds) {
+  const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)lds;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
 struct WaveCtx {
   // loop-invariant per-lane / per-wave values
   unsigned k_read_addr;   // LDS byte offset of this lane's K row with its swizzle term folded in
   unsigned v_read_addr;   // same for the transposed V reads
+  int xor32_addr;         // ds_bpermute address of the lane in the other half holding the same query
   int hf, qi;
   int pos;                // causal horizon of this lane's query row
   float c;                // scale * log2(e)
   int S;                  // number of spans
+  // direct-to-LDS staging
+  const char* kbase;      // k_cache + kv-head offset
+  const char* vbase;
+  unsigned blk_bytes;     // bytes per cache block (all kv heads)
+  unsigned k_gchunk, v_gchunk;  // per-lane byte offset of the (swizzled) 16-byte chunk inside a row
+  int L, last_blk, w, lane;
 };
 
-// ---- one pipelined iteration --------------------------------------------------------------
-// Scur holds the raw scores of tile kt.  Computes (if NEXT) the scores of tile kt+1 into Snext,
-// the softmax update of tile kt and O += P V.
-template <bool MASK, bool NEXT, bool PROBE>
-__device__ __forceinline__ void tile_iter(const WaveCtx& cx, const unsigned char* smem, int kt,
-                                          f32x16 (&Scur)[2], f32x16 (&Snext)[2], const bf16x8 (&qf)[8],
-                                          f32x16 (&O)[4], float& m_run, float& l_run, float (&am)[kMaxSpans],
-                                          const int (&sp_a)[kMaxSpans], const int (&sp_b)[kMaxSpans]) {
-  const int key0 = kt * kTileKeys;
-  const unsigned char* kb = smem + ((kt + 1) & 1) * kTileBytes;             // K of tile kt+1
-  const unsigned char* vb = smem + 2 * kTileBytes + (kt & 1) * kTileBytes;  // V of tile kt
-
-  // -- stage 1: mask and row maximum of the current tile
+// mask (optional) and row maximum of a raw score tile; both lane halves end up with the same value
+template <bool MASK>
+__device__ __forceinline__ float tile_max(const WaveCtx& cx, int key0, f32x16 (&S)[2]) {
   if constexpr (MASK) {
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = key0 + 32 * kbk + 8 * (r >> 2) + 4 * cx.hf + (r & 3);
-        if (key > cx.pos) Scur[kbk][r] = -INFINITY;
+        if (key > cx.pos) S[kbk][r] = -INFINITY;
       }
   }
-  float mx = Scur[0][0];
+  float m0 = fmaxf(S[0][0], S[0][1]), m1 = fmaxf(S[1][0], S[1][1]);
 #pragma unroll
-  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, Scur[0][r]);
+  for (int r = 2; r < 16; r += 2) {
+    m0 = fmaxf(m0, fmaxf(S[0][r], S[0][r + 1]));
+    m1 = fmaxf(m1, fmaxf(S[1][r], S[1][r + 1]));
+  }
+  const float mx = fmaxf(m0, m1);
+  const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(cx.xor32_addr, __float_as_int(mx)));
+  return fmaxf(mx, other);
+}
+
+// Block ids of 64 consecutive blocks (16 tiles) live in one register per lane; two registers
+// cover the group being consumed and the next one.
+struct BlockIds {
+  int grp;
+  int cur, nxt;
+};
+
+__device__ __forceinline__ int load_ids(const int* bt, int first, int lane, int last_blk, int num_blocks) {
+  const int blk = bt[min(first + lane, last_blk)];
+  return ((unsigned)blk < (unsigned)num_blocks) ? blk : 0;
+}
+
+// One direct-to-LDS load: block j of a K or V tile; wave w fills rows 4w..4w+3 of the block.
+// Rows past the last token re-read the last valid row of the last block - finite data that
+// the causal mask hides and that P = 0 multiplies - never the stale tail of a block or a
+// block the sequence does not own.
+__device__ __forceinline__ void issue_block(const WaveCtx& cx, int tile, int j, const char* gbase, unsigned gchunk,
+                                            unsigned long long boff, unsigned char* lds_tile) {
+  const int bidx = min(4 * tile + j, cx.last_blk);
+  const int rmax = cx.L - 1 - 16 * bidx;               // >= 0 because bidx <= last_blk
+  const int r = 4 * cx.w + (cx.lane >> 4);
+  const unsigned off = gchunk + ((unsigned)min(r, rmax) << 8);
+  dma16(gbase + boff, off, lds_tile + (16 * j + 4 * cx.w) * kRowBytes);
+}
+
+__device__ __forceinline__ unsigned long long block_offset(const WaveCtx& cx, int sel, int tile, int j) {
+  const int bidx = min(4 * tile + j, cx.last_blk);      // same 64-block group as block 4 * tile
+  const unsigned blk = (unsigned)__builtin_amdgcn_readlane(sel, bidx & 63);
+  return (unsigned long long)blk * cx.blk_bytes;
+}
+
+__device__ __forceinline__ bf16x8 read_k(const WaveCtx& cx, const unsigned char* kb, int s, int kbk) {
+  const unsigned a = cx.k_read_addr ^ (32u * s);
+  return *reinterpret_cast<const bf16x8*>(kb + a + kbk * 32 * kRowBytes);
+}
+
+__device__ __forceinline__ bf16x8 read_vt(const WaveCtx& cx, const unsigned char* vb, int m, int mb) {
+  const unsigned a = (cx.v_read_addr ^ (64u * mb)) + (16 * m) * kRowBytes;
+  union { v4i16 h[2]; bf16x8 v; } av;
+  av.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16*)(vb + a));
+  av.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) v4i16*)(vb + a + 8 * kRowBytes));
+  return av.v;
+}
+
+__device__ __forceinline__ void qk_tile(const WaveCtx& cx, const unsigned char* kb, const bf16x8 (&qf)[8],
+                                        f32x16 (&S)[2]) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) mx = fmaxf(mx, Scur[1][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float mt = mx * cx.c;
+  for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) S[kbk][r] = 0.0f;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(cx, kb, s, 0), qf[s], S[0], 0, 0, 0);
+    S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(cx, kb, s, 1), qf[s], S[1], 0, 0, 0);
+  }
+}
+
+// ---- one pipelined iteration --------------------------------------------------------------
+// On entry Scur holds the raw (already masked) scores of tile kt and mx_cur their row maximum.
+//   stage B  raise the running reference if needed (rare);
+//   stage C  exponentials of tile kt on the vector ALUs while the matrix cores compute the
+//            scores of tile kt+1 into Snext (8 slices: 2 MFMAs + 4 exponentials each);
+//   stage D  O += P V of tile kt on the matrix cores while the scalar/vector units issue the
+//            direct-to-LDS loads of V(kt+1) and K(kt+2) and reduce the row maximum of tile
+//            kt+1 (16 slices: 1 MFMA + one piece of the other work each).
+// The slices are fenced so the instruction streams stay interleaved as written.  Loads are
+// issued unconditionally with the tile index clamped to the last tile: the buffers they land
+// in are free by then and are never read again.
+// Returns the row maximum of tile kt+1.
+template <bool MASKNEXT, bool NEXT, bool PROBE>
+__device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* smem, int kt, int ntiles,
+                                           BlockIds& ids, const int* bt, int num_blocks,
+                                           unsigned long long (&boff_next)[4],
+                                           f32x16 (&Scur)[2], float mx_cur, f32x16 (&Snext)[2],
+                                           const bf16x8 (&qf)[8], f32x16 (&O)[4], float& m_run, float& l_run,
+                                           float (&am)[kMaxSpans], const int (&sp_a)[kMaxSpans],
+                                           const int (&sp_b)[kMaxSpans]) {
+  const int key0 = kt * kTileKeys;
+  unsigned char* const Kbuf = smem;
+  unsigned char* const Vbuf = smem + 2 * kTileBytes;
+  const unsigned char* kb = Kbuf + ((kt + 1) & 1) * kTileBytes;  // K of tile kt+1
+  const unsigned char* vb = Vbuf + (kt & 1) * kTileBytes;        // V of tile kt
+
+  // K(kt+1) and V(kt) were issued one iteration ago; after the barrier every wave has also
+  // finished reading the buffers that the loads issued below will overwrite
+  wait_vmem();
+  __syncthreads();
+
+  // -- stage B
+  const float mt = mx_cur * cx.c;
   const bool upd = mt > m_run + kLazyTau;
   if (__builtin_amdgcn_ballot_w64(upd) != 0) {
     const float alpha = upd ? fast_exp2(m_run - mt) : 1.0f;
@@ -97,48 +198,56 @@ __device__ __forceinline__ void tile_iter(const WaveCtx& cx, const unsigned char
     for (int s = 0; s < kMaxSpans; ++s) am[s] *= alpha;
   }
   const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;
+  // block-id registers: the K prefetch (two tiles ahead) may enter a new group of 64 blocks
+  const int tk = min(kt + 2, ntiles - 1), tv = min(kt + 1, ntiles - 1);
+  if ((tk >> 4) > ids.grp + 1) {
+    ids.grp += 1;
+    ids.cur = ids.nxt;
+    ids.nxt = load_ids(bt, 64 * (ids.grp + 1), cx.lane, cx.last_blk, num_blocks);
+  }
+  const int sel = ((tk >> 4) == ids.grp) ? ids.cur : ids.nxt;
+  __builtin_amdgcn_sched_barrier(0);
 
-  // -- stage 2: exponentials of tile kt on the vector ALUs, scores of tile kt+1 on the matrix cores
-  if constexpr (NEXT) {
-#pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) Snext[kbk][r] = 0.0f;
+  // -- stage C
+  float tsum = 0.0f;
+  union PB { uint32_t u[4]; bf16x8 v; } pb[4];
+  {
+    bf16x8 ka[2][2];
+    if constexpr (NEXT) {
+      ka[0][0] = read_k(cx, kb, 0, 0);
+      ka[0][1] = read_k(cx, kb, 0, 1);
+    }
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const unsigned a = cx.k_read_addr ^ (32u * s);
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(kb + a);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(kb + a + 32 * kRowBytes);
-      Snext[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[s], Snext[0], 0, 0, 0);
-      Snext[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[s], Snext[1], 0, 0, 0);
+      if constexpr (NEXT) {
+        if (s < 7) {
+          ka[(s + 1) & 1][0] = read_k(cx, kb, s + 1, 0);
+          ka[(s + 1) & 1][1] = read_k(cx, kb, s + 1, 1);
+        }
+        if (s == 0) {
+          const f32x16 z = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+          Snext[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], z, 0, 0, 0);
+          Snext[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][1], qf[0], z, 0, 0, 0);
+        } else {
+          Snext[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][0], qf[s], Snext[0], 0, 0, 0);
+          Snext[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][1], qf[s], Snext[1], 0, 0, 0);
+        }
+      }
+      // exponentials of elements 4s .. 4s+3 of the current tile
+      const int kbk = s >> 2, r0 = 4 * (s & 3);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float ex = fast_exp2(__builtin_fmaf(Scur[kbk][r0 + e], cx.c, -m_safe));
+        Scur[kbk][r0 + e] = ex;
+        tsum += ex;
+      }
+      const int m = 2 * kbk + ((s & 3) >> 1);
+      pb[m].u[2 * (s & 1)] = pack_bf16(Scur[kbk][r0], Scur[kbk][r0 + 1]);
+      pb[m].u[2 * (s & 1) + 1] = pack_bf16(Scur[kbk][r0 + 2], Scur[kbk][r0 + 3]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
-  float tsum = 0.0f;
-#pragma unroll
-  for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float e = fast_exp2(__builtin_fmaf(Scur[kbk][r], cx.c, -m_safe));
-      Scur[kbk][r] = e;
-      tsum += e;
-    }
   l_run += tsum;
-  union PB { uint32_t u[4]; bf16x8 v; } pb[4];
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      pb[m].u[e] = pack_bf16(Scur[m >> 1][8 * (m & 1) + 2 * e], Scur[m >> 1][8 * (m & 1) + 2 * e + 1]);
-  if constexpr (NEXT) {
-    // interleave: one MFMA, its two LDS reads, a slice of the vector work
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU
-    }
-  }
-  __builtin_amdgcn_sched_barrier(0);
 
   if constexpr (PROBE) {
 #pragma unroll
@@ -162,133 +271,113 @@ __device__ __forceinline__ void tile_iter(const WaveCtx& cx, const unsigned char
         }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
 
-  // -- stage 3: O^T += V^T P^T, V read transposed from its natural layout
+  // -- stage D
+  float mxp[8];   // partial maxima of the next tile, 4 scores each
+  if constexpr (NEXT && MASKNEXT) {
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
+    for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-      const unsigned a = (cx.v_read_addr ^ (64u * mb)) + (16 * m) * kRowBytes;
-      union { v4i16 h[2]; bf16x8 v; } av;
-      av.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16*)(vb + a));
-      av.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) v4i16*)(vb + a + 8 * kRowBytes));
-      O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, pb[m].v, O[mb], 0, 0, 0);
-    }
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + kTileKeys + 32 * kbk + 8 * (r >> 2) + 4 * cx.hf + (r & 3);
+        if (key > cx.pos) Snext[kbk][r] = -INFINITY;
+      }
+    __builtin_amdgcn_sched_barrier(0);
   }
+  bf16x8 va[2];
+  va[0] = read_vt(cx, vb, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int m = i >> 2, mb = i & 3;
+    if (i < 15) va[(i + 1) & 1] = read_vt(cx, vb, (i + 1) >> 2, (i + 1) & 3);
+    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i & 1], pb[m].v, O[mb], 0, 0, 0);
+    if (i < 4) {
+      // V(kt+1): block offsets were computed when K(kt+1) was issued
+      issue_block(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
+    } else if (i < 8) {
+      const int j = i - 4;
+      boff_next[j] = block_offset(cx, sel, tk, j);
+      issue_block(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
+    } else if constexpr (NEXT) {
+      const int q = i - 8;   // scores 4q .. 4q+3 of the next tile
+      const int kbk = q >> 2, r0 = 4 * (q & 3);
+      mxp[q] = fmaxf(fmaxf(Snext[kbk][r0], Snext[kbk][r0 + 1]), fmaxf(Snext[kbk][r0 + 2], Snext[kbk][r0 + 3]));
+      asm volatile("" : "+v"(mxp[q]));   // keep the reduction inside its slice
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float mx_next = 0.0f;
+  if constexpr (NEXT) {
+    const float mx = fmaxf(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])),
+                           fmaxf(fmaxf(mxp[4], mxp[5]), fmaxf(mxp[6], mxp[7])));
+    const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(cx.xor32_addr, __float_as_int(mx)));
+    mx_next = fmaxf(mx, other);
+  }
+  return mx_next;
 }
 
 template <bool PROBE>
-__device__ __forceinline__ void run_tiles(const WaveCtx& cx, const unsigned char* smem, int ntiles, int n_nomask,
+__device__ __forceinline__ void run_tiles(const WaveCtx& cx, unsigned char* smem, int ntiles, int n_nomask,
                                           const bf16x8 (&qf)[8], f32x16 (&O)[4], float& m_run, float& l_run,
                                           float (&am)[kMaxSpans], const int (&sp_a)[kMaxSpans],
-                                          const int (&sp_b)[kMaxSpans], const int* bt, int last_blk,
-                                          const char* kbase, const char* vbase, size_t blk_bytes, int num_blocks,
-                                          unsigned k_goff, unsigned v_goff, int L, int w, int lane,
-                                          unsigned char* smem_w) {
-  // block ids of up to 64 consecutive blocks (16 tiles) live in one register per lane
-  int grp = 0;
-  int btv0 = bt[min(lane, last_blk)];
-  int btv1 = bt[min(64 + lane, last_blk)];
-
-  auto block_id = [&](int bidx) -> int {   // bidx uniform, already clamped to last_blk
-    const int g = bidx >> 6;
-    const int v = (g == grp) ? btv0 : btv1;
-    int blk = __builtin_amdgcn_readlane(v, bidx & 63);
-    return ((unsigned)blk < (unsigned)num_blocks) ? blk : 0;
-  };
-  // direct-to-LDS load of one tile (4 blocks of 16 keys): wave w fills rows 4w..4w+3 of each block
-  auto issue = [&](int tile, const char* gbase, unsigned goff, unsigned char* lds_tile) {
-    const int key0 = tile * kTileKeys;
-    if (__builtin_expect(key0 + kTileKeys <= L, 1)) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int blk = block_id(4 * tile + j);
-        const char* src = gbase + (size_t)blk * blk_bytes;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src + goff), LDS_PTR(lds_tile + (16 * j + 4 * w) * kRowBytes),
-                                         16, 0, 0);
-      }
-    } else {
-      // the tile reaches past the last token: rows beyond it re-read the last valid row of
-      // the last block - finite data that the causal mask hides and that P = 0 multiplies -
-      // never the stale tail of a block or a block the sequence does not own
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int bidx = min(4 * tile + j, last_blk);
-        const int blk = block_id(bidx);
-        const char* src = gbase + (size_t)blk * blk_bytes;
-        const int r = 4 * w + (lane >> 4);
-        const int rmax = L - 1 - 16 * bidx;              // >= 0 because bidx <= last_blk
-        const unsigned off = goff - (unsigned)(r - min(r, rmax)) * kRowBytes;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src + off), LDS_PTR(lds_tile + (16 * j + 4 * w) * kRowBytes),
-                                         16, 0, 0);
-      }
-    }
-  };
-  unsigned char* const Kbuf = smem_w;
-  unsigned char* const Vbuf = smem_w + 2 * kTileBytes;
+                                          const int (&sp_b)[kMaxSpans], const int* bt, int num_blocks) {
+  BlockIds ids;
+  ids.grp = 0;
+  ids.cur = load_ids(bt, 0, cx.lane, cx.last_blk, num_blocks);
+  ids.nxt = load_ids(bt, 64, cx.lane, cx.last_blk, num_blocks);
+  unsigned char* const Kbuf = smem;
+  unsigned char* const Vbuf = smem + 2 * kTileBytes;
 
   f32x16 S0[2], S1[2];
+  unsigned long long boff[4];
 
-  issue(0, kbase, k_goff, Kbuf);
-  issue(0, vbase, v_goff, Vbuf);
-  if (ntiles > 1) issue(1, kbase, k_goff, Kbuf + kTileBytes);
+  // prologue: K(0), V(0), K(1) in flight, then the scores of tile 0
+  const int t1 = min(1, ntiles - 1);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    boff[j] = block_offset(cx, ids.cur, 0, j);
+    issue_block(cx, 0, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf);
+    issue_block(cx, 0, j, cx.vbase, cx.v_gchunk, boff[j], Vbuf);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    boff[j] = block_offset(cx, ids.cur, t1, j);
+    issue_block(cx, t1, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf + kTileBytes);
+  }
   wait_vmem();
   __syncthreads();
-  // scores of tile 0
-#pragma unroll
-  for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) S0[kbk][r] = 0.0f;
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const unsigned a = cx.k_read_addr ^ (32u * s);
-    const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(smem + a);
-    const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(smem + a + 32 * kRowBytes);
-    S0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[s], S0[0], 0, 0, 0);
-    S0[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[s], S0[1], 0, 0, 0);
-  }
+  qk_tile(cx, Kbuf, qf, S0);
+  float mx = (n_nomask > 0) ? tile_max<false>(cx, 0, S0) : tile_max<true>(cx, 0, S0);
 
-  auto top = [&](int kt) {
-    wait_vmem();
-    __syncthreads();
-    // rotate the block-id registers when the K prefetch (two tiles ahead) enters a new group
-    if (((kt + 2) >> 4) > grp + 1) {
-      grp += 1;
-      btv0 = btv1;
-      btv1 = bt[min(64 * (grp + 1) + lane, last_blk)];
-    }
-    if (kt + 2 < ntiles) issue(kt + 2, kbase, k_goff, Kbuf + (kt & 1) * kTileBytes);
-    if (kt + 1 < ntiles) issue(kt + 1, vbase, v_goff, Vbuf + ((kt + 1) & 1) * kTileBytes);
-  };
-
+  // tile kt+1 needs no mask while kt+1 < n_nomask
   int kt = 0;
-  const int end_nomask = min(n_nomask, ntiles - 1);
-  // unmasked tiles, two per trip so the score registers ping-pong without copies
+  const int end_nomask = min(n_nomask - 1, ntiles - 1);
+  // two tiles per trip so the score registers ping-pong without copies
   while (kt + 2 <= end_nomask) {
-    top(kt);
-    tile_iter<false, true, PROBE>(cx, smem, kt, S0, S1, qf, O, m_run, l_run, am, sp_a, sp_b);
-    top(kt + 1);
-    tile_iter<false, true, PROBE>(cx, smem, kt + 1, S1, S0, qf, O, m_run, l_run, am, sp_a, sp_b);
+    mx = tile_iter<false, true, PROBE>(cx, smem, kt, ntiles, ids, bt, num_blocks, boff, S0, mx, S1, qf, O, m_run,
+                                       l_run, am, sp_a, sp_b);
+    mx = tile_iter<false, true, PROBE>(cx, smem, kt + 1, ntiles, ids, bt, num_blocks, boff, S1, mx, S0, qf, O,
+                                       m_run, l_run, am, sp_a, sp_b);
     kt += 2;
   }
   if (kt < end_nomask) {
-    top(kt);
-    tile_iter<false, true, PROBE>(cx, smem, kt, S0, S1, qf, O, m_run, l_run, am, sp_a, sp_b);
+    mx = tile_iter<false, true, PROBE>(cx, smem, kt, ntiles, ids, bt, num_blocks, boff, S0, mx, S1, qf, O, m_run,
+                                       l_run, am, sp_a, sp_b);
     S0[0] = S1[0]; S0[1] = S1[1];
     kt += 1;
   }
-  // masked tiles that still have a successor
+  // tiles whose successor needs the causal mask
   while (kt < ntiles - 1) {
-    top(kt);
-    tile_iter<true, true, PROBE>(cx, smem, kt, S0, S1, qf, O, m_run, l_run, am, sp_a, sp_b);
+    mx = tile_iter<true, true, PROBE>(cx, smem, kt, ntiles, ids, bt, num_blocks, boff, S0, mx, S1, qf, O, m_run,
+                                      l_run, am, sp_a, sp_b);
     S0[0] = S1[0]; S0[1] = S1[1];
     kt += 1;
   }
   // last tile
-  top(kt);
-  tile_iter<true, false, PROBE>(cx, smem, kt, S0, S1, qf, O, m_run, l_run, am, sp_a, sp_b);
+  (void)tile_iter<true, false, PROBE>(cx, smem, kt, ntiles, ids, bt, num_blocks, boff, S0, mx, S1, qf, O, m_run,
+                                      l_run, am, sp_a, sp_b);
 }
 
 __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
@@ -319,6 +408,7 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
   const int n_nomask = (wave_pos_min + 1) / kTileKeys;   // tiles whose last key is within every row's horizon
 
   WaveCtx cx;
+  cx.xor32_addr = (lane ^ 32) << 2;
   cx.hf = hf;
   cx.qi = qi;
   cx.pos = L - n + t;
@@ -338,16 +428,19 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
 
   const __bf16* const qg = static_cast<const __bf16*>(p.q);
   const int* const bt = p.block_table + (size_t)seq * p.max_blocks;
-  const size_t blk_bytes = (size_t)p.Hkv * kBlock * D * 2;
-  const char* const kbase = static_cast<const char*>(p.k_cache) + (size_t)kvh * kBlock * D * 2;
-  const char* const vbase = static_cast<const char*>(p.v_cache) + (size_t)kvh * kBlock * D * 2;
-  const int last_blk = (L - 1) >> 4;
+  cx.blk_bytes = (unsigned)p.Hkv * kBlock * D * 2;
+  cx.kbase = static_cast<const char*>(p.k_cache) + (size_t)kvh * kBlock * D * 2;
+  cx.vbase = static_cast<const char*>(p.v_cache) + (size_t)kvh * kBlock * D * 2;
+  cx.L = L;
+  cx.last_blk = (L - 1) >> 4;
+  cx.w = w;
+  cx.lane = lane;
 
   // per-lane source offsets of the direct-to-LDS loads: LDS slot (row r, physical chunk pc)
   // receives logical chunk pc ^ swizzle(r)
   const int r = 4 * w + (lane >> 4), pc = lane & 15;
-  const unsigned k_goff = (unsigned)r * kRowBytes + (unsigned)(pc ^ (r & 15)) * 16;
-  const unsigned v_goff = (unsigned)r * kRowBytes + (unsigned)(pc ^ ((r & 3) << 2)) * 16;
+  cx.k_gchunk = (unsigned)(pc ^ (r & 15)) * 16;
+  cx.v_gchunk = (unsigned)(pc ^ ((r & 3) << 2)) * 16;
 
   bf16x8 qf[8];
   {
@@ -384,15 +477,14 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
   for (int s = 0; s < kMaxSpans; ++s) am[s] = 0.0f;
 
   if (wave_probe)
-    run_tiles<true>(cx, smem, ntiles, n_nomask, qf, O, m_run, l_run, am, sp_a, sp_b, bt, last_blk, kbase, vbase,
-                    blk_bytes, p.num_blocks, k_goff, v_goff, L, w, lane, smem);
+    run_tiles<true>(cx, smem, ntiles, n_nomask, qf, O, m_run, l_run, am, sp_a, sp_b, bt, p.num_blocks);
   else
-    run_tiles<false>(cx, smem, ntiles, n_nomask, qf, O, m_run, l_run, am, sp_a, sp_b, bt, last_blk, kbase, vbase,
-                     blk_bytes, p.num_blocks, k_goff, v_goff, L, w, lane, smem);
+    run_tiles<false>(cx, smem, ntiles, n_nomask, qf, O, m_run, l_run, am, sp_a, sp_b, bt, p.num_blocks);
 
   // epilogue: normalise, transpose through LDS (K buffers, 16-byte chunks swizzled by row), coalesced stores
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.0f / l_tot;
+  wait_vmem();   // the clamped prefetches of the last iterations must have landed before LDS is reused
   __syncthreads();
   unsigned char* const ot = smem + w * (kWaveRows * kRowBytes);
   if (wave_active) {
