@@ -47,7 +47,7 @@ Layout make_layout(const hook_attn_probe_args* a) {
   }
   size_t off = 0;
   l.off_hdr = off;  off = align_up(off + sizeof(PlanHeader));
-  l.off_pf = off;   off = align_up(off + sizeof(WorkItem) * (size_t)l.pf_cap);
+  l.off_pf = off;   off = align_up(off + 2 * sizeof(WorkItem) * (size_t)l.pf_cap);
   l.off_dec = off;  off = align_up(off + sizeof(WorkItem) * (size_t)l.dec_cap);
   l.off_seq = off;  off = align_up(off + sizeof(int2) * (size_t)(a->num_seqs > 0 ? a->num_seqs : 1));
   l.off_part = off;

@@ -35,8 +35,9 @@ struct PlanHeader {
   int pad[12];
 };
 
-// One record per work item.  prefill: {seq, first chunk-local row, L, n};
-// decode: {seq, chunk index, L, global q row}.
+// Work-list records.  prefill: two consecutive records per item,
+// {seq, first chunk-local row, L, n} and {global row of the sequence's first query, 0, 0, 0};
+// decode: one record {seq, chunk index, L, global q row}.
 typedef int4 WorkItem;
 
 struct AttnParams {

@@ -110,7 +110,10 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
         const int last = min(r0 + p.rows_per_wg, s.n) - 1;
         const int tiles = (s.L - s.n + last) / kTileKeys + 1;
         const int slot = atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
-        if (slot < p.pf_cap) p.pf_items[slot] = make_int4(i, r0, s.L, s.n);
+        if (slot < p.pf_cap) {
+          p.pf_items[2 * slot] = make_int4(i, r0, s.L, s.n);
+          p.pf_items[2 * slot + 1] = make_int4(s.row0, 0, 0, 0);
+        }
       }
     } else if (s.kind == 2) {
       const int nch = (s.L + chunk - 1) / chunk;

@@ -50,10 +50,12 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
   const int rest = bid / p.Hkv;
   const int hg = rest % p.hgroups;
   const int item = rest / p.hgroups;
+  // the grid covers the whole item capacity, so both records can be fetched together with
+  // the item count instead of after it
+  const WorkItem it = p.pf_items[2 * item];
+  const int qbase = p.pf_items[2 * item + 1].x;
   if (item >= p.hdr->n_prefill) return;
-  const WorkItem it = p.pf_items[item];
   const int seq = it.x, row0 = it.y, L = it.z, n = it.w;
-  const int qbase = p.cu_q_lens[seq];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
