@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+# HBM traffic per launch (bytes) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
+# (profiles/hbm_traffic_prefill_c2_decode_c3.md).  Set to None whenever the kernel changes.
+TRAFFIC_PREFILL_C2 = 982.5e6
+TRAFFIC_DECODE_C3 = 4863.6e6
 
 
 def causal_pairs(b) -> int:
@@ -95,38 +99,23 @@ def kernel_times(call, steps: int):
     return dict(zip(("plan_ms", "prefill_ms", "decode_ms", "combine_ms"), [a / steps for a in acc]))
 
 
-def oracle_sample(b_dev, max_seconds_hint: float, kind: str):
-    """Time the CPU oracle on a bounded sample of the workload; returns (work, seconds, desc)."""
+def oracle_sample(b_dev, kind: str):
+    """Time the CPU oracle (as it stands, never tuned) on the workload; returns (work, seconds, desc).
+
+    The 8B-shaped prefill batch costs the oracle about 10 s on the machine's host cores, so it is run
+    whole; the decode batch takes well under a second and is also run whole.
+    """
     import oracle
-    import torch
     b = b_dev.to("cpu")
-    cu = b.cu_q_lens.tolist()
-    lens = b.seq_lens.tolist()
     if kind == "prefill":
-        # a stratified sample of rows of every sequence, all heads
-        rows = []
-        per_seq = 6
-        for i in range(b.num_seqs):
-            n = cu[i + 1] - cu[i]
-            for k in range(per_seq):
-                rows.append(cu[i] + min(n - 1, (2 * k + 1) * n // (2 * per_seq)))
-        pairs = 0
-        for r in rows:
-            i = max(j for j in range(b.num_seqs) if cu[j] <= r)
-            n = cu[i + 1] - cu[i]
-            pairs += lens[i] - n + (r - cu[i]) + 1
         t0 = time.perf_counter()
-        oracle.attn_probe_batch(b, rows=rows)
+        oracle.attn_probe_batch(b)
         dt = time.perf_counter() - t0
-        return 4.0 * b.head_dim * b.num_q_heads * pairs, dt, f"{len(rows)} rows ({per_seq} per sequence, all heads)"
-    else:
-        nseq = min(b.num_seqs, 24)
-        rows = [cu[i] for i in range(nseq)]
-        byts = sum(lens[i] for i in range(nseq)) * b.num_kv_heads * b.head_dim * 4.0
-        t0 = time.perf_counter()
-        oracle.attn_probe_batch(b, rows=rows)
-        dt = time.perf_counter() - t0
-        return byts, dt, f"first {nseq} sequences, all heads"
+        return attn_flops(b), dt, f"all {b.total_q} rows x {b.num_q_heads} heads"
+    t0 = time.perf_counter()
+    oracle.attn_probe_batch(b)
+    dt = time.perf_counter() - t0
+    return kv_bytes(b), dt, f"all {b.num_seqs} sequences x {b.num_q_heads} heads"
 
 
 def main() -> int:
@@ -136,8 +125,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5"],
-                    help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON")
+    ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
+                    help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON. "
+                         "'copy' runs a plain 1 GiB device copy, the known-size reference that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -158,6 +149,14 @@ def main() -> int:
     if args.profile_workload:
         wl = args.profile_workload
         steer = None
+        if wl == "copy":
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+            dst = torch.empty_like(src)
+            for _ in range(args.warmup + args.steps):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            print(f"profiled copy: {args.warmup + args.steps} copies of {src.numel()} bytes", file=sys.stderr)
+            return 0
         if wl == "c2":
             b = W.c2_prefill_8b(device=dev)
         elif wl == "c3":
@@ -187,15 +186,15 @@ def main() -> int:
     ov2 = interleaved_overhead(call2, call2_off, max(10, K // 2), 3)
     value = flops2 / (t2["mean_ms"] * 1e-3) / 1e12
     pre_tflops = flops2 / (k2["prefill_ms"] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_prefill<128>", "achieved": pre_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": pre_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+    roofline = {"bound": "mfma", "kernel": "k_prefill128", "achieved": pre_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": pre_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": TRAFFIC_PREFILL_C2,
                 "kernel_ms": k2["prefill_ms"], "flops_per_launch": flops2}
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        work, dt, desc = oracle_sample(b2, 20.0, "prefill")
+        work, dt, desc = oracle_sample(b2, "prefill")
         cpu_baseline = {"value": work / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-                        "kind": "oracle", "sample": f"c2_prefill_8b: {desc}; {dt:.1f} s"}
+                        "kind": "oracle", "sample": f"c2_prefill_8b: {desc}; {dt:.2f} s"}
 
     if "c3" in only:
         b3 = W.c3_decode_8b(device=dev)
@@ -210,16 +209,16 @@ def main() -> int:
             "workload": "c3_decode_8b", "value": by3 / (t3["mean_ms"] * 1e-3) / 1e9, "unit": "GB/s",
             "ms_per_step": t3["mean_ms"], "median_ms": t3["median_ms"], "kernels_ms": k3,
             "roofline": {"bound": "hbm", "kernel": "k_decode<128,4>", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
-                         "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": None,
+                         "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_DECODE_C3,
                          "bytes_per_launch": by3},
             "probe_overhead_pct": ov3["overhead_pct"],
             "workspace_mb": call3.workspace_needed / 2**20,
         }
         if not args.no_cpu_baseline:
-            work, dt, desc = oracle_sample(b3, 20.0, "decode")
+            work, dt, desc = oracle_sample(b3, "decode")
             extra["decode_c3"]["cpu_baseline"] = {"value": work / dt / 1e9, "unit": "GB/s",
                                                   "cores": oracle.num_threads(), "kind": "oracle",
-                                                  "sample": f"c3_decode_8b: {desc}; {dt:.1f} s"}
+                                                  "sample": f"c3_decode_8b: {desc}; {dt:.2f} s"}
         del b3, call3, call3_off
         torch.cuda.empty_cache()
 
