@@ -286,6 +286,7 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
       }
     __builtin_amdgcn_sched_barrier(0);
   }
+  __builtin_amdgcn_s_setprio(2);   // the matrix-core-bound stage wins issue arbitration over the other wave
   bf16x8 va[2];
   va[0] = read_vt(cx, vb, 0, 0);
 #pragma unroll
@@ -293,13 +294,17 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
     const int m = i >> 2, mb = i & 3;
     if (i < 15) va[(i + 1) & 1] = read_vt(cx, vb, (i + 1) >> 2, (i + 1) & 3);
     O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i & 1], pb[m].v, O[mb], 0, 0, 0);
-    if (i < 4) {
-      // V(kt+1): block offsets were computed when K(kt+1) was issued
-      issue_block(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
-    } else if (i < 8) {
-      const int j = i - 4;
-      boff_next[j] = block_offset(cx, sel, tk, j);
-      issue_block(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
+    if (i < 8) {
+      if constexpr (NEXT) {   // the last tile of an item has nothing left to fetch
+        if (i < 4) {
+          // V(kt+1): block offsets were computed when K(kt+1) was issued
+          issue_block(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
+        } else {
+          const int j = i - 4;
+          boff_next[j] = block_offset(cx, sel, tk, j);
+          issue_block(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
+        }
+      }
     } else if constexpr (NEXT) {
       const int q = i - 8;   // scores 4q .. 4q+3 of the next tile
       const int kbk = q >> 2, r0 = 4 * (q & 3);
@@ -308,6 +313,7 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
     }
     __builtin_amdgcn_sched_barrier(0);
   }
+  __builtin_amdgcn_s_setprio(0);
   float mx_next = 0.0f;
   if constexpr (NEXT) {
     const float mx = fmaxf(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])),
@@ -334,19 +340,25 @@ __device__ __forceinline__ void run_tiles(const WaveCtx& cx, unsigned char* smem
   unsigned long long boff[4];
 
   // prologue: K(0), V(0), K(1) in flight, then the scores of tile 0
-  const int t1 = min(1, ntiles - 1);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     boff[j] = block_offset(cx, ids.cur, 0, j);
     issue_block(cx, 0, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf);
-    issue_block(cx, 0, j, cx.vbase, cx.v_gchunk, boff[j], Vbuf);
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    boff[j] = block_offset(cx, ids.cur, t1, j);
-    issue_block(cx, t1, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf + kTileBytes);
+  for (int j = 0; j < 4; ++j) issue_block(cx, 0, j, cx.vbase, cx.v_gchunk, boff[j], Vbuf);
+  if (ntiles > 1) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      boff[j] = block_offset(cx, ids.cur, 1, j);
+      issue_block(cx, 1, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf + kTileBytes);
+    }
   }
-  wait_vmem();
+  // only K(0) has to have landed for the first scores; V(0) and K(1) are waited for at the
+  // top of the first iteration.  Loads complete in issue order, so it is enough to let the 8
+  // (4 when there is no second tile) younger ones stay in flight.
+  if (ntiles > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
   qk_tile(cx, Kbuf, qf, S0);
   float mx = (n_nomask > 0) ? tile_max<false>(cx, 0, S0) : tile_max<true>(cx, 0, S0);
