@@ -14,6 +14,7 @@ namespace hook {
 namespace {
 
 constexpr int kPlanThreads = 1024;
+constexpr int kListCap = 1024;   // queued prefill sequences
 
 struct SeqInfo { int L, n, row0, kind; };  // kind: 0 skip, 1 prefill, 2 decode
 
@@ -45,22 +46,35 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   __shared__ int scan[kPlanBuckets];
   __shared__ int sh_cnt[4];     // decode chunk counts for 256 / 512 / 1024 keys, status
   __shared__ int sh_dec_next;
+  __shared__ int sh_nlist;
+  __shared__ int sh_list[kListCap];
 
   for (int b = tid; b < kPlanBuckets; b += kPlanThreads) hist[b] = 0;
   if (tid < 4) sh_cnt[tid] = 0;
-  if (tid == 0) sh_dec_next = 0;
+  if (tid == 0) { sh_dec_next = 0; sh_nlist = 0; }
   __syncthreads();
 
   // pass 1: histogram of prefill items by tile count, decode chunk counts per candidate size
+  // Decode sequences are handled one per thread.  Prefill sequences are queued (up to
+  // kListCap; the overflow is handled by the thread that found it) and then taken one per
+  // wave with the lanes spread over the row blocks, so a single long sequence does not loop
+  // in one thread.
+  const int wave = tid >> 6, lane = tid & 63;
+  constexpr int kWaves = kPlanThreads / 64;
   int status = 0;
   int c256 = 0, c512 = 0, c1024 = 0;
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
     const SeqInfo s = read_seq(p, i, &status);
     if (s.kind == 1) {
-      for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
-        const int last = min(r0 + p.rows_per_wg, s.n) - 1;
-        const int tiles = (s.L - s.n + last) / kTileKeys + 1;
-        atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+      const int pos = atomicAdd(&sh_nlist, 1);
+      if (pos < kListCap) {
+        sh_list[pos] = i;
+      } else {
+        for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
+          const int last = min(r0 + p.rows_per_wg, s.n) - 1;
+          const int tiles = (s.L - s.n + last) / kTileKeys + 1;
+          atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+        }
       }
     } else if (s.kind == 2) {
       c256 += (s.L + 255) / 256;
@@ -71,11 +85,25 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   if (c256) { atomicAdd(&sh_cnt[0], c256); atomicAdd(&sh_cnt[1], c512); atomicAdd(&sh_cnt[2], c1024); }
   if (status) atomicOr(&sh_cnt[3], status);
   __syncthreads();
+  const int nlist = min(sh_nlist, kListCap);
+  for (int k = wave; k < nlist; k += kWaves) {
+    int dummy = 0;
+    const SeqInfo s = read_seq(p, sh_list[k], &dummy);
+    for (int r0 = lane * p.rows_per_wg; r0 < s.n; r0 += 64 * p.rows_per_wg) {
+      const int last = min(r0 + p.rows_per_wg, s.n) - 1;
+      const int tiles = (s.L - s.n + last) / kTileKeys + 1;
+      atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+    }
+  }
+  __syncthreads();
 
-  // descending exclusive offsets: scan[b] = number of items in buckets above b
+  // descending exclusive offsets: scan[b] = number of items in buckets above b.  Only buckets
+  // up to the longest possible sequence can be populated; they sit at the END of the reversed
+  // array, so the Hillis-Steele steps needed are those that reach across that populated tail.
   for (int b = tid; b < kPlanBuckets; b += kPlanThreads) scan[b] = hist[kPlanBuckets - 1 - b];
   __syncthreads();
-  for (int off = 1; off < kPlanBuckets; off <<= 1) {
+  const int max_bucket = min(kPlanBuckets - 1, (p.max_blocks * kBlock - 1) / kTileKeys + 1);
+  for (int off = 1; off <= max_bucket; off <<= 1) {
     int v[kPlanBuckets / kPlanThreads];
 #pragma unroll
     for (int k = 0; k < kPlanBuckets / kPlanThreads; ++k) {
@@ -105,17 +133,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     int dummy = 0;
     const SeqInfo s = read_seq(p, i, &dummy);
     int2 sd = make_int2(0, 0);
-    if (s.kind == 1) {
-      for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
-        const int last = min(r0 + p.rows_per_wg, s.n) - 1;
-        const int tiles = (s.L - s.n + last) / kTileKeys + 1;
-        const int slot = atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
-        if (slot < p.pf_cap) {
-          p.pf_items[2 * slot] = make_int4(i, r0, s.L, s.n);
-          p.pf_items[2 * slot + 1] = make_int4(s.row0, 0, 0, 0);
-        }
-      }
-    } else if (s.kind == 2) {
+    if (s.kind == 2) {
       const int nch = (s.L + chunk - 1) / chunk;
       const int base = atomicAdd(&sh_dec_next, nch);
       if (base + nch <= p.dec_cap) {
@@ -124,6 +142,33 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       }
     }
     p.seq_dec[i] = sd;
+  }
+  auto scatter_rows = [&](int i, const SeqInfo& s, int first, int step) {
+    for (int r0 = first * p.rows_per_wg; r0 < s.n; r0 += step * p.rows_per_wg) {
+      const int last = min(r0 + p.rows_per_wg, s.n) - 1;
+      const int tiles = (s.L - s.n + last) / kTileKeys + 1;
+      const int slot = atomicAdd(&hist[min(tiles, kPlanBuckets - 1)], 1);
+      if (slot < p.pf_cap) {
+        p.pf_items[2 * slot] = make_int4(i, r0, s.L, s.n);
+        p.pf_items[2 * slot + 1] = make_int4(s.row0, 0, 0, 0);
+      }
+    }
+  };
+  for (int k = wave; k < nlist; k += kWaves) {
+    int dummy = 0;
+    const int i = sh_list[k];
+    const SeqInfo s = read_seq(p, i, &dummy);
+    scatter_rows(i, s, lane, 64);
+  }
+  if (sh_nlist > kListCap) {   // sequences that did not fit the queue
+    for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
+      int dummy = 0;
+      const SeqInfo s = read_seq(p, i, &dummy);
+      if (s.kind != 1) continue;
+      bool queued = false;
+      for (int k = 0; k < kListCap && !queued; ++k) queued = (sh_list[k] == i);
+      if (!queued) scatter_rows(i, s, 0, 1);
+    }
   }
   __syncthreads();
   if (tid == 0) {

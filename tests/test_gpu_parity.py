@@ -185,3 +185,81 @@ def test_c4_full_size_sampled_rows():
 def test_c5_full_size_sampled_rows():
     b, s = W.c5_mixed()
     _check(b, rows=_sample_rows(b, 24, 4), label="c5_full")
+
+
+# ---- malformed device-side contents must be made safe, flagged and never fault ----
+
+def test_bad_lengths_are_flagged_and_skipped():
+    from paper_2603_06588_amd import binding
+    b_cpu = W.random_batch(160, [200, 300, 150, 90], [200, 1, 150, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=3,
+                           max_sel_q=4, max_spans=2)
+    ref = b_cpu.to(DEV)
+    out_ok, mass_ok = run_hip(ref)
+    bad = b_cpu.to(DEV)
+    bad.seq_lens = bad.seq_lens.clone()
+    bad.seq_lens[2] = 100                      # n_i (150) > L_i: sequence 2 is skipped
+    bad.seq_lens[3] = 16 * b_cpu.max_blocks_per_seq + 500   # beyond the table: clamped
+    bad.block_table = bad.block_table.clone()
+    bad.block_table[3] = torch.where(bad.block_table[3] > b_cpu.num_blocks, torch.zeros_like(bad.block_table[3]),
+                                     bad.block_table[3])
+    out = torch.full_like(out_ok, 7.0)
+    call = binding.call_from_batch(bad, out=out)
+    call.launch()
+    torch.cuda.synchronize()
+    bits_ = call.device_status()
+    assert bits_ & 1 and bits_ & 2
+    cu = b_cpu.cu_q_lens.tolist()
+    # untouched rows of the skipped sequence, bit-identical rows of the valid ones
+    assert (out[cu[2]:cu[3]] == 7.0).all()
+    assert torch.equal(bits(out[cu[0]:cu[2]]), bits(out_ok[cu[0]:cu[2]]))
+    # (sequence 3 attends to whatever the clamped table rows point at: its values are undefined,
+    # the point is that the call completed without touching memory outside the cache)
+    assert torch.equal(bits(call.mass[:2]), bits(mass_ok[:2]))
+    assert (call.mass[2] == 0).all()
+
+
+def test_garbage_block_ids_do_not_fault():
+    b_cpu = W.random_batch(161, [260, 700], [260, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=2, poison=False)
+    b = b_cpu.to(DEV)
+    b.block_table = torch.full_like(b.block_table, 0x7FFFFFF0)
+    b.block_table[0, 0] = -5
+    out, mass = run_hip(b)      # values are meaningless, but every access stays inside the cache
+    assert out.shape == b.q.shape
+
+
+# ---- the call is a fixed launch sequence: it can be replayed from a HIP graph ----
+
+def test_hip_graph_replay_matches_eager():
+    from paper_2603_06588_amd import binding
+    b_cpu = W.random_batch(170, [400, 900, 128, 333], [400, 1, 128, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=4,
+                           max_sel_q=4, max_spans=2)
+    b = b_cpu.to(DEV)
+    eager_out, eager_mass = run_hip(b)
+    call = binding.call_from_batch(b)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        call.launch(s)              # warm-up on the side stream (sets kernel attributes)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        call.launch(torch.cuda.current_stream())
+    for rep in range(3):
+        call.out.fill_(float("nan"))
+        call.mass.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bits(call.out), bits(eager_out)), rep
+        assert torch.equal(bits(call.mass), bits(eager_mass)), rep
+        # eager work between replays
+        again_out, _ = run_hip(b)
+        assert torch.equal(bits(again_out), bits(eager_out))
+
+
+def test_many_prefill_sequences_overflow_the_planner_queue():
+    # more prefill sequences than the planner's queue holds: the overflow path must give the same result
+    nseq = 1100
+    lens = [2 + (i % 5) for i in range(nseq)]
+    b = W.random_batch(180, lens, lens, 4, 2, 128, torch.bfloat16, num_probe_heads=2, max_sel_q=2, max_spans=1)
+    _check(b, label="planner_overflow")
