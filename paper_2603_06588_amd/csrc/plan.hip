@@ -5,7 +5,8 @@
 //   prefill items  one per (sequence with n_i >= 2, block of rows_per_wg query rows), ordered
 //                  by decreasing number of key tiles (longest first) with a counting sort;
 //   decode items   one per (sequence with n_i == 1, chunk of chunk_keys keys); the chunk size
-//                  is picked so that the decode grid has enough workgroups to fill the chip.
+//                  (256..2048) is the largest that still gives the decode grid enough workgroups
+//                  to fill the chip.
 // The same launch zero-fills `mass`.
 #include "hook_device.h"
 
@@ -44,13 +45,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
 
   __shared__ int hist[kPlanBuckets];
   __shared__ int scan[kPlanBuckets];
-  __shared__ int sh_cnt[4];     // decode chunk counts for 256 / 512 / 1024 keys, status
+  __shared__ int sh_cnt[5];     // decode chunk counts for 512 / 1024 / 2048 keys (unused slot), status in [3]
   __shared__ int sh_dec_next;
   __shared__ int sh_nlist;
   __shared__ int sh_list[kListCap];
 
   for (int b = tid; b < kPlanBuckets; b += kPlanThreads) hist[b] = 0;
-  if (tid < 4) sh_cnt[tid] = 0;
+  if (tid < 5) sh_cnt[tid] = 0;
   if (tid == 0) { sh_dec_next = 0; sh_nlist = 0; }
   __syncthreads();
 
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   const int wave = tid >> 6, lane = tid & 63;
   constexpr int kWaves = kPlanThreads / 64;
   int status = 0;
-  int c256 = 0, c512 = 0, c1024 = 0;
+  int c512 = 0, c1024 = 0, c2048 = 0;
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
     const SeqInfo s = read_seq(p, i, &status);
     if (s.kind == 1) {
@@ -77,12 +78,12 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
         }
       }
     } else if (s.kind == 2) {
-      c256 += (s.L + 255) / 256;
       c512 += (s.L + 511) / 512;
       c1024 += (s.L + 1023) / 1024;
+      c2048 += (s.L + 2047) / 2048;
     }
   }
-  if (c256) { atomicAdd(&sh_cnt[0], c256); atomicAdd(&sh_cnt[1], c512); atomicAdd(&sh_cnt[2], c1024); }
+  if (c512) { atomicAdd(&sh_cnt[0], c512); atomicAdd(&sh_cnt[1], c1024); atomicAdd(&sh_cnt[2], c2048); }
   if (status) atomicOr(&sh_cnt[3], status);
   __syncthreads();
   const int nlist = min(sh_nlist, kListCap);
@@ -121,11 +122,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     const int rb = kPlanBuckets - 1 - b;  // position of bucket b in the reversed order
     hist[b] = scan[rb] - hist[b];         // exclusive start (hist[b] still holds the count)
   }
-  // chunk size: the largest candidate that still yields >= 4096 decode workgroups, else 256
+  // chunk size: long chunks stream best, so take the largest candidate that still yields at
+  // least 2048 decode workgroups (8 per CU), else 256 keys
   const int wg_per_item = p.Hkv * p.dec_hgroups;
   int chunk = 256;
-  if ((long long)sh_cnt[2] * wg_per_item >= 4096) chunk = 1024;
-  else if ((long long)sh_cnt[1] * wg_per_item >= 4096) chunk = 512;
+  if ((long long)sh_cnt[2] * wg_per_item >= 2048) chunk = 2048;
+  else if ((long long)sh_cnt[1] * wg_per_item >= 2048) chunk = 1024;
+  else if ((long long)sh_cnt[0] * wg_per_item >= 2048) chunk = 512;
   __syncthreads();
 
   // pass 2: scatter
