@@ -171,6 +171,20 @@ hook_status hook_attn_probe_device_status(const void* workspace, void* stream, i
 hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t* token_mask,
                        int32_t num_tokens, int32_t hidden_dim, int32_t dtype, void* stream);
 
+/*
+ * Measurement aids for callers that report roofline fractions (bench.py): what the chip
+ * sustains on the two resources the kernels are bound by.  Both launch one kernel on
+ * `stream` and return at once; the caller times them.
+ *   hook_probe_mfma_bf16  num_workgroups x 4 waves issue independent 32x32x16 bf16 MFMAs back
+ *                         to back for `iters` rounds of 16; *flops (HOST) receives the flop
+ *                         count of the launch.  `sink` is 4 bytes of device memory (never
+ *                         written in practice).
+ *   hook_probe_hbm_read   streams `bytes` (multiple of 16, 16-byte aligned) from `src` once
+ *                         with 16-byte loads; `sink` as above.
+ */
+hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* sink, void* stream, double* flops);
+hook_status hook_probe_hbm_read(const void* src, size_t bytes, void* sink, void* stream);
+
 const char* hook_status_string(hook_status status);
 int hook_version(void);
 

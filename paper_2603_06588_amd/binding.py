@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
            "hook_attn_probe_device_status",
-           "hook_steer", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -70,6 +70,11 @@ def load_library() -> ctypes.CDLL:
         lib.hook_steer.restype = ctypes.c_int
         lib.hook_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        lib.hook_probe_mfma_bf16.restype = ctypes.c_int
+        lib.hook_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.POINTER(ctypes.c_double)]
+        lib.hook_probe_hbm_read.restype = ctypes.c_int
+        lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_status_string.restype = ctypes.c_char_p
         lib.hook_status_string.argtypes = [ctypes.c_int]
         lib.hook_version.restype = ctypes.c_int
@@ -181,6 +186,25 @@ def call_from_batch(b, probe: bool = True, **kw) -> AttnProbeCall:
     return AttnProbeCall(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
                          b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
                          b.key_spans, b.scale, **kw)
+
+
+def probe_mfma_bf16(iters: int, num_workgroups: int, sink: torch.Tensor, stream=None) -> float:
+    """Launch the back-to-back MFMA probe; returns the flop count of the launch."""
+    flops = ctypes.c_double(0.0)
+    st = load_library().hook_probe_mfma_bf16(int(iters), int(num_workgroups), _p(sink), _stream_handle(stream),
+                                             ctypes.byref(flops))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_probe_mfma_bf16")
+    return float(flops.value)
+
+
+def probe_hbm_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
+    """Launch the streaming-read probe over `src`; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    st = load_library().hook_probe_hbm_read(_p(src), nbytes, _p(sink), _stream_handle(stream))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_probe_hbm_read")
+    return nbytes
 
 
 def hook_steer(hidden: torch.Tensor, vec: torch.Tensor, alpha: float, token_mask: torch.Tensor,

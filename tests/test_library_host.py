@@ -19,7 +19,7 @@ def binding():
 
 def test_exports_every_declared_symbol(binding):
     header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
-    declared = set(re.findall(r"\b(hook_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(hook_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     lib = binding.load_library()
     for name in declared:
