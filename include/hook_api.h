@@ -185,6 +185,58 @@ hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t
 hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* sink, void* stream, double* flops);
 hook_status hook_probe_hbm_read(const void* src, size_t bytes, void* sink, void* stream);
 
+/*
+ * Compact q/k capture: the literal output of the paper's passive hook (Section 2.1, qkv_hook:
+ * per hooked layer the queries of the last token or of all tokens and ALL keys, split per
+ * batch item), gathered on the device into dense buffers instead of being copied out whole.
+ *   q_out[i, p, t - query_sel[i,0], :] = q[cu_q_lens[i] + t, probe_heads[p], :]
+ *       for t in [query_sel[i,0], query_sel[i,1]) (at most max_sel_q rows, chunk-local);
+ *       entries without a selected row are zero-filled.
+ *   k_out[cu_k_lens[i] + j, c, :] = k_cache[block_table[i, j / B], capture_kv_heads[c], j % B, :]
+ *       for j in [0, L_i): the keys of the chosen kv heads, sequences back to back.
+ * All arrays are DEVICE pointers, caller-owned; cu_k_lens holds the prefix sums of seq_lens
+ * (cu_k_lens[num_seqs] = total_k, which the host needs anyway to size k_out).  Pure data
+ * movement: outputs are bit-identical to the inputs they copy.  Asynchronous on `stream`.
+ * Block ids outside [0, num_blocks) are clamped as in hook_attn_probe.
+ */
+typedef struct hook_capture_qk_args {
+  int32_t num_seqs, total_q, num_q_heads, num_kv_heads, head_dim, block_size;
+  int32_t max_blocks_per_seq, num_blocks, dtype;
+  const void*    q;                 /* [total_q, Hq, d] */
+  const void*    k_cache;           /* [num_blocks, Hkv, B, d] */
+  const int32_t* block_table;       /* [num_seqs, max_blocks_per_seq] */
+  const int32_t* seq_lens;          /* [num_seqs] */
+  const int32_t* cu_q_lens;         /* [num_seqs + 1] */
+  int32_t        num_probe_heads;   /* P (0: no q capture) */
+  const int32_t* probe_heads;       /* [P] */
+  int32_t        max_sel_q;         /* NQ */
+  const int32_t* query_sel;         /* [num_seqs, 2] */
+  int32_t        num_capture_kv_heads;  /* KH (0: no k capture) */
+  const int32_t* capture_kv_heads;  /* [KH] kv head indices */
+  const int32_t* cu_k_lens;         /* [num_seqs + 1] */
+  int32_t        total_k;
+  void* q_out;                      /* [num_seqs, P, NQ, d] */
+  void* k_out;                      /* [total_k, KH, d] */
+  void* stream;
+} hook_capture_qk_args;
+
+hook_status hook_capture_qk(const hook_capture_qk_args* args);
+
+/*
+ * Host helper: parses the layer/heads string of the paper's worker configuration
+ * (Section 2.1, `_parse_layer_heads`: '0:0,3,6;15:2' means layer 0 heads 0, 3, 6 and layer 15
+ * head 2) into (layer, head) pairs in the order written.  All pointers are HOST pointers.
+ *   text      NUL-terminated string; blanks around numbers and empty ';' parts are ignored
+ *   layers, heads   arrays of `capacity` entries (may be null when capacity is 0)
+ *   *count    receives the number of pairs in the string, also when it exceeds `capacity`
+ * Returns HOOK_ERR_SHAPE for a malformed string (missing ':', empty head list, non-digits,
+ * values above 2^30) and HOOK_ERR_WORKSPACE when the pairs do not fit `capacity` (the first
+ * `capacity` pairs are written).  One hook_attn_probe call covers one layer: the caller passes
+ * the heads of that layer, sorted, as probe_heads.
+ */
+hook_status hook_parse_layer_heads(const char* text, int32_t* layers, int32_t* heads, int32_t capacity,
+                                   int32_t* count);
+
 const char* hook_status_string(hook_status status);
 int hook_version(void);
 

@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
            "hook_attn_probe_device_status",
-           "hook_steer", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_capture_qk", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -38,6 +38,21 @@ class HookAttnProbeArgs(ctypes.Structure):
         ("out", ctypes.c_void_p), ("mass", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
+    ]
+
+
+class HookCaptureQkArgs(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("total_q", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("max_blocks_per_seq", ctypes.c_int32), ("num_blocks", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("q", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+        ("seq_lens", ctypes.c_void_p), ("cu_q_lens", ctypes.c_void_p),
+        ("num_probe_heads", ctypes.c_int32), ("probe_heads", ctypes.c_void_p),
+        ("max_sel_q", ctypes.c_int32), ("query_sel", ctypes.c_void_p),
+        ("num_capture_kv_heads", ctypes.c_int32), ("capture_kv_heads", ctypes.c_void_p),
+        ("cu_k_lens", ctypes.c_void_p), ("total_k", ctypes.c_int32),
+        ("q_out", ctypes.c_void_p), ("k_out", ctypes.c_void_p), ("stream", ctypes.c_void_p),
     ]
 
 
@@ -75,6 +90,12 @@ def load_library() -> ctypes.CDLL:
                                              ctypes.POINTER(ctypes.c_double)]
         lib.hook_probe_hbm_read.restype = ctypes.c_int
         lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        lib.hook_capture_qk.restype = ctypes.c_int
+        lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
+        lib.hook_parse_layer_heads.restype = ctypes.c_int
+        lib.hook_parse_layer_heads.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32),
+                                               ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+                                               ctypes.POINTER(ctypes.c_int32)]
         lib.hook_status_string.restype = ctypes.c_char_p
         lib.hook_status_string.argtypes = [ctypes.c_int]
         lib.hook_version.restype = ctypes.c_int
@@ -186,6 +207,56 @@ def call_from_batch(b, probe: bool = True, **kw) -> AttnProbeCall:
     return AttnProbeCall(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
                          b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
                          b.key_spans, b.scale, **kw)
+
+
+def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel,
+                    capture_kv_heads, cu_k_lens, total_k: int, stream=None, q_out=None, k_out=None):
+    """Gather (q_out [num_seqs, P, NQ, d], k_out [total_k, KH, d]); total_k is a host integer."""
+    lib = load_library()
+    total_q, Hq, d = q.shape
+    num_blocks, Hkv, B, _ = k_cache.shape
+    num_seqs, max_blocks = block_table.shape
+    P = int(probe_heads.numel()) if probe_heads is not None else 0
+    KH = int(capture_kv_heads.numel()) if capture_kv_heads is not None else 0
+    if q_out is None:
+        q_out = torch.empty((num_seqs, P, int(max_sel_q), d), dtype=q.dtype, device=q.device)
+    if k_out is None:
+        k_out = torch.empty((int(total_k), KH, d), dtype=q.dtype, device=q.device)
+    a = HookCaptureQkArgs()
+    a.num_seqs, a.total_q, a.num_q_heads, a.num_kv_heads = num_seqs, total_q, Hq, Hkv
+    a.head_dim, a.block_size, a.max_blocks_per_seq, a.num_blocks = d, B, max_blocks, num_blocks
+    a.dtype = _DT[q.dtype]
+    a.q, a.k_cache, a.block_table = _p(q), _p(k_cache), _p(block_table)
+    a.seq_lens, a.cu_q_lens = _p(seq_lens), _p(cu_q_lens)
+    a.num_probe_heads, a.probe_heads, a.max_sel_q, a.query_sel = P, _p(probe_heads), int(max_sel_q), _p(query_sel)
+    a.num_capture_kv_heads, a.capture_kv_heads = KH, _p(capture_kv_heads)
+    a.cu_k_lens, a.total_k = _p(cu_k_lens), int(total_k)
+    a.q_out, a.k_out, a.stream = _p(q_out), _p(k_out), _stream_handle(stream)
+    st = lib.hook_capture_qk(ctypes.byref(a))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_capture_qk")
+    return q_out, k_out
+
+
+def parse_layer_heads(text: str):
+    """'0:0,3,6;15:2' -> [(0, 0), (0, 3), (0, 6), (15, 2)] (parsed by the library)."""
+    lib = load_library()
+    count = ctypes.c_int32(0)
+    st = lib.hook_parse_layer_heads(text.encode(), None, None, 0, ctypes.byref(count))
+    if st not in (HOOK_OK, 4):
+        raise HookError(st, "hook_parse_layer_heads")
+    n = int(count.value)
+    layers, heads = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
+    st = lib.hook_parse_layer_heads(text.encode(), layers, heads, n, ctypes.byref(count))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_parse_layer_heads")
+    return [(int(layers[i]), int(heads[i])) for i in range(n)]
+
+
+def probe_heads_for_layer(pairs, layer: int, device="cpu") -> torch.Tensor:
+    """Sorted, de-duplicated heads of one layer as the int32 probe_heads tensor of a call."""
+    hs = sorted({int(h) for (l, h) in pairs if int(l) == int(layer)})
+    return torch.tensor(hs, dtype=torch.int32, device=device)
 
 
 def probe_mfma_bf16(iters: int, num_workgroups: int, sink: torch.Tensor, stream=None) -> float:

@@ -178,6 +178,52 @@ hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t
                       static_cast<hipStream_t>(stream)) == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
 }
 
+hook_status hook_parse_layer_heads(const char* text, int32_t* layers, int32_t* heads, int32_t capacity,
+                                   int32_t* count) {
+  if (!text || !count || capacity < 0 || (capacity > 0 && (!layers || !heads))) return HOOK_ERR_NULL;
+  *count = 0;
+  const char* c = text;
+  auto skip_blank = [&]() { while (*c == ' ' || *c == '\t' || *c == '\n' || *c == '\r') ++c; };
+  auto number = [&](int32_t* out) -> bool {   // blanks, digits, blanks
+    skip_blank();
+    if (*c < '0' || *c > '9') return false;
+    long long v = 0;
+    while (*c >= '0' && *c <= '9') {
+      v = v * 10 + (*c - '0');
+      if (v > (1ll << 30)) return false;
+      ++c;
+    }
+    skip_blank();
+    *out = (int32_t)v;
+    return true;
+  };
+  int32_t n = 0;
+  for (;;) {
+    skip_blank();
+    if (*c == '\0') break;
+    if (*c == ';') { ++c; continue; }          // empty part
+    int32_t layer = 0;
+    if (!number(&layer) || *c != ':') return HOOK_ERR_SHAPE;
+    ++c;
+    int32_t in_part = 0;
+    for (;;) {
+      int32_t head = 0;
+      if (!number(&head)) return HOOK_ERR_SHAPE;
+      if (n < capacity) { layers[n] = layer; heads[n] = head; }
+      ++n;
+      ++in_part;
+      if (*c == ',') { ++c; continue; }
+      break;
+    }
+    if (in_part == 0) return HOOK_ERR_SHAPE;
+    if (*c == ';') { ++c; continue; }
+    if (*c == '\0') break;
+    return HOOK_ERR_SHAPE;
+  }
+  *count = n;
+  return n > capacity ? HOOK_ERR_WORKSPACE : HOOK_OK;
+}
+
 const char* hook_status_string(hook_status s) {
   switch (s) {
     case HOOK_OK: return "ok";

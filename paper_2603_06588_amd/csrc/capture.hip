@@ -1,0 +1,117 @@
+// Compact q/k capture: gathers the queries of probed heads on selected rows and all keys of
+// chosen kv heads from the paged cache into dense buffers.  Pure HBM streaming: every thread
+// moves 16 bytes, 16 consecutive lanes one (token, head) row.
+#include "../../include/hook_api.h"
+#include "hook_device.h"
+
+namespace hook {
+namespace {
+
+struct CaptureParams {
+  int num_seqs, total_q, Hq, Hkv, max_blocks, num_blocks, row_chunks;  // row_chunks = d * esize / 16
+  const uint4* q;
+  const uint4* k_cache;
+  const int* block_table;
+  const int* seq_lens;
+  const int* cu_q_lens;
+  int P;
+  const int* probe_heads;
+  int NQ;
+  const int* query_sel;
+  int KH;
+  const int* kv_heads;
+  const int* cu_k_lens;
+  int total_k;
+  uint4* q_out;
+  uint4* k_out;
+};
+
+// one thread per 16-byte chunk of k_out; a workgroup handles 256 / row_chunks rows
+__global__ __launch_bounds__(256) void k_capture_k(const CaptureParams p) {
+  const int rc = p.row_chunks;
+  const long long chunk = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long row = chunk / rc;                 // (token, c) row of k_out
+  const int cc = (int)(chunk % rc);
+  if (row >= (long long)p.total_k * p.KH) return;
+  const int tok = (int)(row / p.KH), c = (int)(row % p.KH);
+  // sequence of this token: largest i with cu_k_lens[i] <= tok
+  int lo = 0, hi = p.num_seqs;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (p.cu_k_lens[mid] <= tok) lo = mid; else hi = mid;
+  }
+  const int j = tok - p.cu_k_lens[lo];
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (j >= 0 && j < p.seq_lens[lo] && j < p.max_blocks * kBlock) {
+    int blk = p.block_table[(size_t)lo * p.max_blocks + (j >> 4)];
+    blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
+    int g = p.kv_heads[c];
+    g = ((unsigned)g < (unsigned)p.Hkv) ? g : 0;
+    v = p.k_cache[(((size_t)blk * p.Hkv + g) * kBlock + (j & 15)) * rc + cc];
+  }
+  p.k_out[(size_t)row * rc + cc] = v;
+}
+
+// one thread per 16-byte chunk of q_out
+__global__ __launch_bounds__(256) void k_capture_q(const CaptureParams p) {
+  const int rc = p.row_chunks;
+  const long long chunk = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long row = chunk / rc;                 // (i, p, tt)
+  const int cc = (int)(chunk % rc);
+  if (row >= (long long)p.num_seqs * p.P * p.NQ) return;
+  const int tt = (int)(row % p.NQ);
+  const int ps = (int)((row / p.NQ) % p.P);
+  const int i = (int)(row / ((long long)p.NQ * p.P));
+  const int qb = p.query_sel[2 * i], qe = p.query_sel[2 * i + 1];
+  const int row0 = p.cu_q_lens[i], n = p.cu_q_lens[i + 1] - row0;
+  const int t = qb + tt;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  int h = p.probe_heads[ps];
+  if (t >= 0 && t < qe && t < n && (unsigned)h < (unsigned)p.Hq && row0 >= 0 && row0 + t < p.total_q)
+    v = p.q[((size_t)(row0 + t) * p.Hq + h) * rc + cc];
+  p.q_out[(size_t)row * rc + cc] = v;
+}
+
+}  // namespace
+}  // namespace hook
+
+extern "C" hook_status hook_capture_qk(const hook_capture_qk_args* a) {
+  using namespace hook;
+  if (!a) return HOOK_ERR_NULL;
+  if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->head_dim <= 0 ||
+      a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->total_k < 0 || a->num_probe_heads < 0 ||
+      a->num_capture_kv_heads < 0)
+    return HOOK_ERR_SHAPE;
+  if (a->block_size != HOOK_BLOCK_SIZE) return HOOK_ERR_UNSUPPORTED;
+  if (a->dtype != HOOK_BF16 && a->dtype != HOOK_F32) return HOOK_ERR_UNSUPPORTED;
+  const int esize = a->dtype == HOOK_BF16 ? 2 : 4;
+  if ((a->head_dim * esize) % 16 != 0) return HOOK_ERR_UNSUPPORTED;
+  if (a->num_probe_heads > 0 && (a->max_sel_q < 1 || a->max_sel_q > HOOK_MAX_SEL_Q)) return HOOK_ERR_SHAPE;
+  if (a->num_seqs == 0) return HOOK_OK;
+  CaptureParams p{};
+  p.num_seqs = a->num_seqs; p.total_q = a->total_q; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads;
+  p.max_blocks = a->max_blocks_per_seq; p.num_blocks = a->num_blocks;
+  p.row_chunks = a->head_dim * esize / 16;
+  p.q = static_cast<const uint4*>(a->q); p.k_cache = static_cast<const uint4*>(a->k_cache);
+  p.block_table = a->block_table; p.seq_lens = a->seq_lens; p.cu_q_lens = a->cu_q_lens;
+  p.P = a->num_probe_heads; p.probe_heads = a->probe_heads; p.NQ = a->max_sel_q; p.query_sel = a->query_sel;
+  p.KH = a->num_capture_kv_heads; p.kv_heads = a->capture_kv_heads; p.cu_k_lens = a->cu_k_lens;
+  p.total_k = a->total_k;
+  p.q_out = static_cast<uint4*>(a->q_out); p.k_out = static_cast<uint4*>(a->k_out);
+  hipStream_t st = static_cast<hipStream_t>(a->stream);
+  if (p.P > 0) {
+    if (!a->q || !a->cu_q_lens || !a->probe_heads || !a->query_sel || !a->q_out) return HOOK_ERR_NULL;
+    const long long chunks = (long long)p.num_seqs * p.P * p.NQ * p.row_chunks;
+    hipLaunchKernelGGL(k_capture_q, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
+    if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
+  }
+  if (p.KH > 0 && p.total_k > 0) {
+    if (!a->k_cache || !a->block_table || !a->seq_lens || !a->capture_kv_heads || !a->cu_k_lens || !a->k_out)
+      return HOOK_ERR_NULL;
+    const long long chunks = (long long)p.total_k * p.KH * p.row_chunks;
+    if ((chunks + 255) / 256 > 0x7FFFFFFFll) return HOOK_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_capture_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
+    if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
+  }
+  return HOOK_OK;
+}

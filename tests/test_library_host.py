@@ -35,6 +35,29 @@ def test_args_struct_matches_header_field_order(binding):
     assert fields == [f[0] for f in binding.HookAttnProbeArgs._fields_]
 
 
+def test_capture_struct_matches_header_field_order(binding):
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    body = header[header.index("typedef struct hook_capture_qk_args {"):header.index("} hook_capture_qk_args;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for stmt in body.split("{", 1)[1].split(";"):
+        stmt = stmt.strip()
+        if not stmt:
+            continue
+        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
+        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    assert names == [f[0] for f in binding.HookCaptureQkArgs._fields_]
+    lib = binding.load_library()
+    a = binding.HookCaptureQkArgs()
+    assert lib.hook_capture_qk(None) == 1
+    a.num_seqs, a.num_q_heads, a.num_kv_heads, a.head_dim, a.block_size = 1, 8, 2, 128, 32
+    a.max_blocks_per_seq, a.num_blocks = 4, 4
+    assert lib.hook_capture_qk(ctypes.byref(a)) == 3          # block size
+    a.block_size = 16
+    a.num_probe_heads, a.max_sel_q = 2, 1
+    assert lib.hook_capture_qk(ctypes.byref(a)) == 1          # null arrays
+
+
 def _args(binding, **kw):
     a = binding.HookAttnProbeArgs()
     base = dict(num_seqs=2, total_q=10, num_q_heads=8, num_kv_heads=2, head_dim=128, block_size=16,

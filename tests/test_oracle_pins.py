@@ -409,3 +409,32 @@ def test_steer_exact_rational_arithmetic(dtype):
                 nb = [near, np.nextafter(near, np.float32(np.inf)), np.nextafter(near, np.float32(-np.inf))]
                 best = min(nb, key=lambda z: abs(Fraction(float(z)) - exact))
                 assert abs(Fraction(got) - exact) <= abs(Fraction(float(best)) - exact)
+
+
+# --------------------------------------------------------------------------
+# compact q/k capture reference: pinned by torch indexing on an identity table
+# --------------------------------------------------------------------------
+
+def test_capture_reference_against_slicing():
+    from oracle.capture import capture_qk
+    lens, qlens = [37, 64, 5], [37, 3, 1]
+    b = W.random_batch(91, lens, qlens, 8, 4, 16, torch.bfloat16, num_probe_heads=3, max_sel_q=4, shuffle=False,
+                       poison=False)
+    kvh = torch.tensor([3, 0], dtype=torch.int32)
+    q_out, k_out, cu_k = capture_qk(b.q, b.k_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads,
+                                    b.max_sel_q, b.query_sel, kvh)
+    assert cu_k.tolist() == [0, 37, 101, 106]
+    # identity table: sequence i owns consecutive blocks, so its keys are a reshape of the cache
+    first_blk = 0
+    for i, L in enumerate(lens):
+        nb = (L + 15) // 16
+        dense = b.k_cache[first_blk:first_blk + nb].permute(0, 2, 1, 3).reshape(nb * 16, 4, 16)[:L]
+        assert torch.equal(k_out[cu_k[i]:cu_k[i + 1]].view(torch.int16), dense[:, kvh.long()].view(torch.int16))
+        first_blk += nb
+    cu = b.cu_q_lens.tolist()
+    for i in range(3):
+        qb, qe = b.query_sel[i].tolist()
+        rows = list(range(qb, min(qe, qlens[i])))[:4]
+        want = b.q[cu[i]:cu[i + 1]][rows][:, b.probe_heads.long()].permute(1, 0, 2)
+        assert torch.equal(q_out[i, :, :len(rows)].view(torch.int16), want.view(torch.int16))
+        assert (q_out[i, :, len(rows):] == 0).all()
