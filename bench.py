@@ -231,6 +231,22 @@ def main() -> int:
             "probe_overhead_pct": ov3["overhead_pct"],
             "workspace_mb": call3.workspace_needed / 2**20,
         }
+        # compact q/k capture on the same batch: every key of every kv head, the probed heads' queries
+        kvh = torch.arange(b3.num_kv_heads, dtype=torch.int32, device=dev)
+        cu_k = torch.zeros(b3.num_seqs + 1, dtype=torch.int32, device=dev)
+        cu_k[1:] = torch.cumsum(b3.seq_lens, 0)
+        total_k = int(cu_k[-1])
+        q_out, k_out = binding.hook_capture_qk(b3.q, b3.k_cache, b3.block_table, b3.seq_lens, b3.cu_q_lens,
+                                               b3.probe_heads, b3.max_sel_q, b3.query_sel, kvh, cu_k, total_k)
+        tcap = time_call(lambda: binding.hook_capture_qk(
+            b3.q, b3.k_cache, b3.block_table, b3.seq_lens, b3.cu_q_lens, b3.probe_heads, b3.max_sel_q,
+            b3.query_sel, kvh, cu_k, total_k, q_out=q_out, k_out=k_out), K, Wm)
+        cap_bytes = 2.0 * (k_out.numel() + q_out.numel()) * k_out.element_size()   # read once + written once
+        extra["capture_qk_c3"] = {
+            "workload": "c3_decode_8b, all kv heads", "ms": tcap["mean_ms"], "bytes": cap_bytes,
+            "gbs": cap_bytes / (tcap["mean_ms"] * 1e-3) / 1e9,
+            "frac_of_hbm_peak": cap_bytes / (tcap["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        del q_out, k_out
         if not args.no_cpu_baseline:
             work, dt, desc = oracle_sample(b3, "decode")
             extra["decode_c3"]["cpu_baseline"] = {"value": work / dt / 1e9, "unit": "GB/s",

@@ -1,6 +1,6 @@
 // Compact q/k capture: gathers the queries of probed heads on selected rows and all keys of
-// chosen kv heads from the paged cache into dense buffers.  Pure HBM streaming: every thread
-// moves 16 bytes, 16 consecutive lanes one (token, head) row.
+// chosen kv heads from the paged cache into dense buffers.  Pure HBM streaming: 16-byte chunks,
+// consecutive lanes on consecutive chunks of a (token, head) row.
 #include "../../include/hook_api.h"
 #include "hook_device.h"
 
@@ -26,30 +26,62 @@ struct CaptureParams {
   uint4* k_out;
 };
 
-// one thread per 16-byte chunk of k_out; a workgroup handles 256 / row_chunks rows
+// A workgroup moves kTokTile consecutive rows of k_out (all chosen heads): its first lanes find
+// each token's sequence (binary search in cu_k_lens) and cache block, then every thread keeps up
+// to kInFlight 16-byte loads in flight.  Destination chunks are consecutive over the whole tile;
+// each source row (one token of one head) is a contiguous d-element run.
+constexpr int kTokTile = 16;
+constexpr int kInFlight = 8;
+
 __global__ __launch_bounds__(256) void k_capture_k(const CaptureParams p) {
+  __shared__ long long src_row[kTokTile];   // (blk * Hkv) * kBlock + slot, or -1 for a zero row
   const int rc = p.row_chunks;
-  const long long chunk = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long row = chunk / rc;                 // (token, c) row of k_out
-  const int cc = (int)(chunk % rc);
-  if (row >= (long long)p.total_k * p.KH) return;
-  const int tok = (int)(row / p.KH), c = (int)(row % p.KH);
-  // sequence of this token: largest i with cu_k_lens[i] <= tok
-  int lo = 0, hi = p.num_seqs;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (p.cu_k_lens[mid] <= tok) lo = mid; else hi = mid;
+  const int tok0 = blockIdx.x * kTokTile;
+  if (threadIdx.x < kTokTile) {
+    const int tok = tok0 + threadIdx.x;
+    long long r = -1;
+    if (tok < p.total_k) {
+      // sequence of this token: largest i with cu_k_lens[i] <= tok
+      int lo = 0, hi = p.num_seqs;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (p.cu_k_lens[mid] <= tok) lo = mid; else hi = mid;
+      }
+      const int j = tok - p.cu_k_lens[lo];
+      if (j >= 0 && j < p.seq_lens[lo] && j < p.max_blocks * kBlock) {
+        int blk = p.block_table[(size_t)lo * p.max_blocks + (j >> 4)];
+        blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
+        r = (long long)blk * p.Hkv * kBlock + (j & 15);
+      }
+    }
+    src_row[threadIdx.x] = r;
   }
-  const int j = tok - p.cu_k_lens[lo];
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (j >= 0 && j < p.seq_lens[lo] && j < p.max_blocks * kBlock) {
-    int blk = p.block_table[(size_t)lo * p.max_blocks + (j >> 4)];
-    blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
-    int g = p.kv_heads[c];
-    g = ((unsigned)g < (unsigned)p.Hkv) ? g : 0;
-    v = p.k_cache[(((size_t)blk * p.Hkv + g) * kBlock + (j & 15)) * rc + cc];
+  __syncthreads();
+  const int ntok = min(kTokTile, p.total_k - tok0);
+  const int row_stride = p.KH * rc;            // chunks per token in k_out
+  const int nchunks = ntok * row_stride;
+  uint4* dst = p.k_out + (size_t)tok0 * row_stride;
+  for (int base = threadIdx.x; base < nchunks; base += 256 * kInFlight) {
+    uint4 v[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const int idx = base + u * 256;
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (idx < nchunks) {
+        const int ts = idx / row_stride, rem = idx - ts * row_stride;
+        const int c = rem / rc, cc = rem - c * rc;
+        const long long r = src_row[ts];
+        int g = p.kv_heads[c];
+        g = ((unsigned)g < (unsigned)p.Hkv) ? g : 0;
+        if (r >= 0) v[u] = p.k_cache[(size_t)(r + (long long)g * kBlock) * rc + cc];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const int idx = base + u * 256;
+      if (idx < nchunks) dst[idx] = v[u];
+    }
   }
-  p.k_out[(size_t)row * rc + cc] = v;
 }
 
 // one thread per 16-byte chunk of q_out
@@ -108,9 +140,8 @@ extern "C" hook_status hook_capture_qk(const hook_capture_qk_args* a) {
   if (p.KH > 0 && p.total_k > 0) {
     if (!a->k_cache || !a->block_table || !a->seq_lens || !a->capture_kv_heads || !a->cu_k_lens || !a->k_out)
       return HOOK_ERR_NULL;
-    const long long chunks = (long long)p.total_k * p.KH * p.row_chunks;
-    if ((chunks + 255) / 256 > 0x7FFFFFFFll) return HOOK_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_capture_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
+    if ((long long)kTokTile * p.KH * p.row_chunks > 0x7FFFFFFFll) return HOOK_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_capture_k, dim3((unsigned)((p.total_k + kTokTile - 1) / kTokTile)), dim3(256), 0, st, p);
     if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
   }
   return HOOK_OK;
