@@ -121,8 +121,8 @@ def oracle_sample(b_dev, kind: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
@@ -224,7 +224,7 @@ def main() -> int:
         dec_gbs = by3 / (k3["decode_ms"] * 1e-3) / 1e9
         extra["decode_c3"] = {
             "workload": "c3_decode_8b", "value": by3 / (t3["mean_ms"] * 1e-3) / 1e9, "unit": "GB/s",
-            "ms_per_step": t3["mean_ms"], "median_ms": t3["median_ms"], "kernels_ms": k3,
+            "ms_per_step": t3["mean_ms"], "median_ms": t3["median_ms"], "min_ms": t3["min_ms"], "kernels_ms": k3,
             "roofline": {"bound": "hbm", "kernel": "k_decode<128,4>", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_DECODE_C3,
                          "bytes_per_launch": by3},
@@ -270,6 +270,23 @@ def main() -> int:
             "frac_of_mfma_peak": fl4 / (k4["prefill_ms"] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
             "probe_overhead_pct": ov4["overhead_pct"],
         }
+        if not args.no_cpu_baseline:
+            # the whole batch would cost the oracle minutes: all probed rows, the rows on either side of a
+            # few tile boundaries and 128 seeded-random rows, for every head; scaled by causal-pair count
+            n4 = b4.total_q
+            g = torch.Generator().manual_seed(3)
+            rows = sorted(set(range(n4 - 32, n4)) | {0, 63, 64, 255, 256, n4 // 2 - 1, n4 // 2}
+                          | set(torch.randint(0, n4, (128,), generator=g).tolist()))
+            b4c = b4.to("cpu")
+            t0 = time.perf_counter()
+            oracle.attn_probe_batch(b4c, rows=rows)
+            dt = time.perf_counter() - t0
+            work = 4.0 * b4.head_dim * b4.num_q_heads * sum(r + 1 for r in rows)
+            extra["long_prefill_c4"]["cpu_baseline"] = {
+                "value": work / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"c4_long_prefill_70b: {len(rows)} of {n4} rows x {b4.num_q_heads} heads; {dt:.2f} s; "
+                          f"extrapolated whole batch {fl4 / (work / dt):.0f} s"}
+            del b4c
         del b4, call4, call4_off
         torch.cuda.empty_cache()
 
@@ -308,10 +325,22 @@ def main() -> int:
                       "frac_of_hbm_peak": steer_bytes / (t5s["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                       "bytes": steer_bytes, "buffers_rotated": 4},
         }
+        if not args.no_cpu_baseline:
+            b5c, s5c = b5.to("cpu"), s5.to("cpu")
+            t0 = time.perf_counter()
+            oracle.attn_probe_batch(b5c)
+            dt_a = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            oracle.steer_batch(s5c)
+            dt_s = time.perf_counter() - t0
+            extra["mixed_c5"]["cpu_baseline"] = {
+                "value": (dt_a + dt_s) * 1e3, "unit": "ms per step", "cores": oracle.num_threads(),
+                "kind": "oracle", "sample": f"c5_mixed whole: attention {dt_a:.2f} s, steering {dt_s:.3f} s",
+                "steer_gbs": steer_bytes / dt_s / 1e9}
 
     line = {
         "metric": "hooked_attn_prefill_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": K, "warmup": Wm, "ms_per_step": t2["mean_ms"], "median_ms": t2["median_ms"],
+        "steps": K, "warmup": Wm, "ms_per_step": t2["mean_ms"], "median_ms": t2["median_ms"], "min_ms": t2["min_ms"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "c2_prefill_8b: 16 ragged prefills U[512,2048], 32q/8kv heads, d128, paged KV "
                                "block 16 shuffled, 12 probed heads, last 8 rows, 1 span",

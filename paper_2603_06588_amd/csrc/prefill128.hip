@@ -110,12 +110,23 @@ __device__ __forceinline__ int load_ids(const int* bt, int first, int lane, int 
 // Rows past the last token re-read the last valid row of the last block - finite data that
 // the causal mask hides and that P = 0 multiplies - never the stale tail of a block or a
 // block the sequence does not own.
+//
+// That row clamp is needed for V only (0 * NaN would poison the output).  A K row past the last
+// token may hold anything: it only produces scores of keys beyond every row's horizon, and
+// those are overwritten with -inf before use; the row still lies inside a block the sequence
+// owns.  So K is fetched with a loop-invariant per-lane offset.
+template <bool CLAMP_ROWS>
 __device__ __forceinline__ void issue_block(const WaveCtx& cx, int tile, int j, const char* gbase, unsigned gchunk,
                                             unsigned long long boff, unsigned char* lds_tile) {
-  const int bidx = min(4 * tile + j, cx.last_blk);
-  const int rmax = cx.L - 1 - 16 * bidx;               // >= 0 because bidx <= last_blk
   const int r = 4 * cx.w + (cx.lane >> 4);
-  const unsigned off = gchunk + ((unsigned)min(r, rmax) << 8);
+  unsigned off;
+  if constexpr (CLAMP_ROWS) {
+    const int bidx = min(4 * tile + j, cx.last_blk);
+    const int rmax = cx.L - 1 - 16 * bidx;             // >= 0 because bidx <= last_blk
+    off = gchunk + ((unsigned)min(r, rmax) << 8);
+  } else {
+    off = gchunk + ((unsigned)r << 8);
+  }
   dma16(gbase + boff, off, lds_tile + (16 * j + 4 * cx.w) * kRowBytes);
 }
 
@@ -275,7 +286,7 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
   }
 
   // -- stage D
-  float mxp[8];   // partial maxima of the next tile, 4 scores each
+  float mx_acc = -INFINITY;   // running maximum of the next tile's scores
   if constexpr (NEXT && MASKNEXT) {
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk)
@@ -298,26 +309,27 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
       if constexpr (NEXT) {   // the last tile of an item has nothing left to fetch
         if (i < 4) {
           // V(kt+1): block offsets were computed when K(kt+1) was issued
-          issue_block(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
+          issue_block<true>(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
         } else {
           const int j = i - 4;
           boff_next[j] = block_offset(cx, sel, tk, j);
-          issue_block(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
+          issue_block<false>(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
         }
       }
     } else if constexpr (NEXT) {
       const int q = i - 8;   // scores 4q .. 4q+3 of the next tile
       const int kbk = q >> 2, r0 = 4 * (q & 3);
-      mxp[q] = fmaxf(fmaxf(Snext[kbk][r0], Snext[kbk][r0 + 1]), fmaxf(Snext[kbk][r0 + 2], Snext[kbk][r0 + 3]));
-      asm volatile("" : "+v"(mxp[q]));   // keep the reduction inside its slice
+      // three-operand maximum written out: fmaxf() would first canonicalise every score with a
+      // v_max of its own; volatile keeps the reduction inside its slice
+      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mx_acc) : "v"(Snext[kbk][r0]), "v"(Snext[kbk][r0 + 1]));
+      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mx_acc) : "v"(Snext[kbk][r0 + 2]), "v"(Snext[kbk][r0 + 3]));
     }
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_setprio(0);
   float mx_next = 0.0f;
   if constexpr (NEXT) {
-    const float mx = fmaxf(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])),
-                           fmaxf(fmaxf(mxp[4], mxp[5]), fmaxf(mxp[6], mxp[7])));
+    const float mx = mx_acc;
     const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(cx.xor32_addr, __float_as_int(mx)));
     mx_next = fmaxf(mx, other);
   }
@@ -343,15 +355,15 @@ __device__ __forceinline__ void run_tiles(const WaveCtx& cx, unsigned char* smem
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     boff[j] = block_offset(cx, ids.cur, 0, j);
-    issue_block(cx, 0, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf);
+    issue_block<false>(cx, 0, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf);
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) issue_block(cx, 0, j, cx.vbase, cx.v_gchunk, boff[j], Vbuf);
+  for (int j = 0; j < 4; ++j) issue_block<true>(cx, 0, j, cx.vbase, cx.v_gchunk, boff[j], Vbuf);
   if (ntiles > 1) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       boff[j] = block_offset(cx, ids.cur, 1, j);
-      issue_block(cx, 1, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf + kTileBytes);
+      issue_block<false>(cx, 1, j, cx.kbase, cx.k_gchunk, boff[j], Kbuf + kTileBytes);
     }
   }
   // only K(0) has to have landed for the first scores; V(0) and K(1) are waited for at the
