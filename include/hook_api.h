@@ -223,6 +223,47 @@ typedef struct hook_capture_qk_args {
 hook_status hook_capture_qk(const hook_capture_qk_args* args);
 
 /*
+ * Score reductions over the mass tensor of one hook_attn_probe call (Section 2.2, analyzer:
+ * the captured attention is aggregated over the token ranges of each prompt and reduced to a
+ * score; Section 2, config file: the reduction is an average or a weighted sum; Section 3:
+ * focus score of the important heads on the instruction, per-document relevance for the
+ * re-ranker).  The paper elides the formula, so the reading is a choice of the caller:
+ *   HOOK_REDUCE_SPAN_MEAN      scores[i, r] = sum_p w_p * mean_t mass[i, p, t, r]        [num_seqs, S]
+ *   HOOK_REDUCE_RATIO_MEAN     scores[i] = sum_p w_p * mean_t a / (a + b)                [num_seqs]
+ *   HOOK_REDUCE_RATIO_OF_SUMS  scores[i] = A / (A + B), A = sum_p w_p * mean_t a, B alike [num_seqs]
+ * with a = mass[i, p, t, span_a], b = mass[i, p, t, span_b]; a ratio whose denominator is 0
+ * counts as 0.  mean_t runs over the rows the probe call selected for sequence i:
+ * t in [0, min(query_sel[i,1], n_i, query_sel[i,0] + NQ) - max(query_sel[i,0], 0)), or all NQ
+ * rows when query_sel is null; a sequence without selected rows scores 0.  w_p is
+ * head_weights[p], or 1 / P (the average) when head_weights is null.  With accumulate != 0
+ * the result is added to `scores` instead of stored, which sums layers (one call each, the
+ * layer weight folded into head_weights) and subtracts a calibration pass (negated weights).
+ * Sums run in fp32 in a fixed order, so results are reproducible bit for bit.
+ * All arrays are DEVICE pointers, caller-owned; asynchronous on `stream`.
+ */
+typedef enum hook_reduce_mode {
+  HOOK_REDUCE_SPAN_MEAN = 0,
+  HOOK_REDUCE_RATIO_MEAN = 1,
+  HOOK_REDUCE_RATIO_OF_SUMS = 2
+} hook_reduce_mode;
+
+typedef struct hook_reduce_args {
+  int32_t num_seqs, num_probe_heads, max_sel_q, max_spans;   /* shape of mass: [num_seqs, P, NQ, S] */
+  const float*   mass;
+  const int32_t* query_sel;       /* [num_seqs, 2] as passed to the probe call, or null */
+  const int32_t* cu_q_lens;       /* [num_seqs + 1] as passed to the probe call, or null (then rows are
+                                     limited by query_sel and NQ only) */
+  const float*   head_weights;    /* [P] or null */
+  int32_t        mode;            /* hook_reduce_mode */
+  int32_t        span_a, span_b;  /* ratio modes only: indices in [0, S) */
+  int32_t        accumulate;
+  float*         scores;          /* [num_seqs, S] (SPAN_MEAN) or [num_seqs] */
+  void*          stream;
+} hook_reduce_args;
+
+hook_status hook_reduce_mass(const hook_reduce_args* args);
+
+/*
  * Host helper: parses the layer/heads string of the paper's worker configuration
  * (Section 2.1, `_parse_layer_heads`: '0:0,3,6;15:2' means layer 0 heads 0, 3, 6 and layer 15
  * head 2) into (layer, head) pairs in the order written.  All pointers are HOST pointers.

@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
            "hook_attn_probe_device_status",
-           "hook_steer", "hook_capture_qk", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -54,6 +54,21 @@ class HookCaptureQkArgs(ctypes.Structure):
         ("cu_k_lens", ctypes.c_void_p), ("total_k", ctypes.c_int32),
         ("q_out", ctypes.c_void_p), ("k_out", ctypes.c_void_p), ("stream", ctypes.c_void_p),
     ]
+
+
+class HookReduceArgs(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("num_probe_heads", ctypes.c_int32), ("max_sel_q", ctypes.c_int32),
+        ("max_spans", ctypes.c_int32),
+        ("mass", ctypes.c_void_p), ("query_sel", ctypes.c_void_p), ("cu_q_lens", ctypes.c_void_p),
+        ("head_weights", ctypes.c_void_p),
+        ("mode", ctypes.c_int32), ("span_a", ctypes.c_int32), ("span_b", ctypes.c_int32),
+        ("accumulate", ctypes.c_int32),
+        ("scores", ctypes.c_void_p), ("stream", ctypes.c_void_p),
+    ]
+
+
+REDUCE_SPAN_MEAN, REDUCE_RATIO_MEAN, REDUCE_RATIO_OF_SUMS = 0, 1, 2
 
 
 class HookError(RuntimeError):
@@ -92,6 +107,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_capture_qk.restype = ctypes.c_int
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
+        lib.hook_reduce_mass.restype = ctypes.c_int
+        lib.hook_reduce_mass.argtypes = [ctypes.POINTER(HookReduceArgs)]
         lib.hook_parse_layer_heads.restype = ctypes.c_int
         lib.hook_parse_layer_heads.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32),
                                                ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
@@ -236,6 +253,27 @@ def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, m
     if st != HOOK_OK:
         raise HookError(st, "hook_capture_qk")
     return q_out, k_out
+
+
+def hook_reduce_mass(mass, mode: int, span_a: int = 0, span_b: int = 1, query_sel=None, cu_q_lens=None,
+                     head_weights=None, scores=None, accumulate: bool = False, stream=None):
+    """Reduce mass [num_seqs, P, NQ, S] to scores ([num_seqs, S] for SPAN_MEAN, else [num_seqs])."""
+    lib = load_library()
+    num_seqs, P, NQ, S = mass.shape
+    if scores is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing scores tensor")
+        shape = (num_seqs, S) if mode == REDUCE_SPAN_MEAN else (num_seqs,)
+        scores = torch.empty(shape, dtype=torch.float32, device=mass.device)
+    a = HookReduceArgs()
+    a.num_seqs, a.num_probe_heads, a.max_sel_q, a.max_spans = num_seqs, P, NQ, S
+    a.mass, a.query_sel, a.cu_q_lens, a.head_weights = _p(mass), _p(query_sel), _p(cu_q_lens), _p(head_weights)
+    a.mode, a.span_a, a.span_b, a.accumulate = int(mode), int(span_a), int(span_b), int(bool(accumulate))
+    a.scores, a.stream = _p(scores), _stream_handle(stream)
+    st = lib.hook_reduce_mass(ctypes.byref(a))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_reduce_mass")
+    return scores
 
 
 def parse_layer_heads(text: str):

@@ -58,6 +58,34 @@ def test_capture_struct_matches_header_field_order(binding):
     assert lib.hook_capture_qk(ctypes.byref(a)) == 1          # null arrays
 
 
+def test_reduce_struct_and_argument_checks(binding):
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    body = header[header.index("typedef struct hook_reduce_args {"):header.index("} hook_reduce_args;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for stmt in body.split("{", 1)[1].split(";"):
+        stmt = stmt.strip()
+        if not stmt:
+            continue
+        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
+        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    assert names == [f[0] for f in binding.HookReduceArgs._fields_]
+    lib = binding.load_library()
+    assert lib.hook_reduce_mass(None) == 1
+    a = binding.HookReduceArgs()
+    a.num_seqs, a.num_probe_heads, a.max_sel_q, a.max_spans = 2, 4, 1, 2
+    a.mode, a.span_a, a.span_b = 1, 0, 1
+    assert lib.hook_reduce_mass(ctypes.byref(a)) == 1          # null mass / scores
+    a.span_b = 2
+    assert lib.hook_reduce_mass(ctypes.byref(a)) == 2          # span index out of range
+    a.span_b, a.mode = 1, 7
+    assert lib.hook_reduce_mass(ctypes.byref(a)) == 3          # unknown mode
+    a.mode, a.max_spans = 0, 9
+    assert lib.hook_reduce_mass(ctypes.byref(a)) == 2          # more spans than the compiled bound
+    a.max_spans, a.num_seqs = 2, 0
+    assert lib.hook_reduce_mass(ctypes.byref(a)) == 0          # empty batch: nothing to do
+
+
 def _args(binding, **kw):
     a = binding.HookAttnProbeArgs()
     base = dict(num_seqs=2, total_q=10, num_q_heads=8, num_kv_heads=2, head_dim=128, block_size=16,
