@@ -325,6 +325,28 @@ def main() -> int:
                       "frac_of_hbm_peak": steer_bytes / (t5s["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                       "bytes": steer_bytes, "buffers_rotated": 4},
         }
+        # steering folded into the residual add that writes hidden: every row read (hidden, delta) and
+        # written once, the steered rows cost nothing extra
+        deltas = [torch.randn_like(s5.hidden) for _ in range(4)]
+
+        def fused_step():
+            binding.hook_residual_add_steer(hiddens[state["i"] % 4], deltas[state["i"] % 4], s5.vec, s5.alpha,
+                                            s5.token_mask)
+            state["i"] += 1
+
+        def unfused_step():
+            hiddens[state["i"] % 4].add_(deltas[state["i"] % 4])
+            binding.hook_steer(hiddens[state["i"] % 4], s5.vec, s5.alpha, s5.token_mask)
+            state["i"] += 1
+
+        t5f = time_call(fused_step, K, Wm)
+        t5u = time_call(unfused_step, K, Wm)
+        fused_bytes = 3.0 * s5.hidden.numel() * s5.hidden.element_size()
+        extra["mixed_c5"]["residual_add_steer"] = {
+            "ms": t5f["mean_ms"], "bytes": fused_bytes, "gbs": fused_bytes / (t5f["mean_ms"] * 1e-3) / 1e9,
+            "frac_of_hbm_peak": fused_bytes / (t5f["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "separate_add_then_steer_ms": t5u["mean_ms"], "buffers_rotated": 4}
+        del deltas
         if not args.no_cpu_baseline:
             b5c, s5c = b5.to("cpu"), s5.to("cpu")
             t0 = time.perf_counter()

@@ -172,6 +172,25 @@ hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t
                        int32_t num_tokens, int32_t hidden_dim, int32_t dtype, void* stream);
 
 /*
+ * Steering folded into the residual add that produces the hidden state (the producer of the
+ * activations that Section 1 "Model Steering" / Section 3 modify), so the steered rows cost
+ * no memory traffic of their own:
+ *   hidden[t, :] = hidden[t, :] + delta[t, :]                          for every row t
+ *                  + alpha * vec[:]   on rows with token_mask[t] != 0
+ * The terms are added in fp64 (alpha * vec is exact there) and rounded ONCE to the storage
+ * dtype, round-to-nearest-even.  token_mask may be null and alpha may be 0: then this is the
+ * plain residual add (vec is not read).
+ *   hidden      [num_tokens, hidden_dim], in place, device
+ *   delta       [num_tokens, hidden_dim], dtype of hidden, device, read only
+ *   vec         [hidden_dim], dtype of hidden, device
+ *   token_mask  [num_tokens] bytes, device, or null
+ * hidden_dim must be a multiple of 8 (bf16) or 4 (f32); hidden, delta, vec 16-byte aligned.
+ */
+hook_status hook_residual_add_steer(void* hidden, const void* delta, const void* vec, float alpha,
+                                    const uint8_t* token_mask, int32_t num_tokens, int32_t hidden_dim,
+                                    int32_t dtype, void* stream);
+
+/*
  * Measurement aids for callers that report roofline fractions (bench.py): what the chip
  * sustains on the two resources the kernels are bound by.  Both launch one kernel on
  * `stream` and return at once; the caller times them.

@@ -1,6 +1,6 @@
 """CPU oracle (test infrastructure only; never imported by the product path)."""
-from .oracle import (attn_probe, attn_probe_batch, steer, steer_batch, round_bf16, num_threads,
+from .oracle import (attn_probe, attn_probe_batch, steer, steer_batch, residual_steer, round_bf16, num_threads,
                      build_oracle, lib_path)
 
-__all__ = ["attn_probe", "attn_probe_batch", "steer", "steer_batch", "round_bf16", "num_threads",
+__all__ = ["attn_probe", "attn_probe_batch", "steer", "steer_batch", "residual_steer", "round_bf16", "num_threads",
            "build_oracle", "lib_path"]

@@ -218,5 +218,27 @@ int hook_oracle_steer(const void* hidden, const void* vec, float alpha, const ui
   return 0;
 }
 
+/*
+ * Steering folded into the residual add that writes the hidden state (the "next" fused form):
+ * out[t,:] = round_to_dtype((double)hidden[t,:] + (double)delta[t,:] [+ (double)alpha * (double)vec[:]])
+ * with the bracket on rows whose token_mask byte is non-zero; one rounding, nearest-even.
+ * token_mask may be null (no row is steered).
+ */
+int hook_oracle_residual_steer(const void* hidden, const void* delta, const void* vec, float alpha,
+                               const uint8_t* token_mask, int T, int D, int dtype, void* hidden_out) {
+  if (dtype != ORACLE_BF16 && dtype != ORACLE_F32) return -2;
+  for (int t = 0; t < T; ++t) {
+    const size_t base = (size_t)t * D;
+    const int on = token_mask && token_mask[t] && alpha != 0.0f;
+    for (int c = 0; c < D; ++c) {
+      double r = load_elem(hidden, base + c, dtype) + load_elem(delta, base + c, dtype);
+      if (on) r += (double)alpha * load_elem(vec, (size_t)c, dtype);
+      if (dtype == ORACLE_F32) ((float*)hidden_out)[base + c] = (float)r;
+      else ((uint16_t*)hidden_out)[base + c] = double_to_bf16_rne(r);
+    }
+  }
+  return 0;
+}
+
 /* Exposed so a test can pin the rounding step on its own. */
 uint16_t hook_oracle_round_bf16(double x) { return double_to_bf16_rne(x); }

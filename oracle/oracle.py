@@ -47,6 +47,8 @@ def _load():
                                                                          i32, vp, vp, vp]
         lib.hook_oracle_steer.restype = i32
         lib.hook_oracle_steer.argtypes = [vp, vp, ctypes.c_float, vp, i32, i32, i32, vp]
+        lib.hook_oracle_residual_steer.restype = i32
+        lib.hook_oracle_residual_steer.argtypes = [vp, vp, vp, ctypes.c_float, vp, i32, i32, i32, vp]
         lib.hook_oracle_round_bf16.restype = ctypes.c_uint16
         lib.hook_oracle_round_bf16.argtypes = [dbl]
         lib.hook_oracle_num_threads.restype = i32
@@ -127,6 +129,23 @@ def steer(hidden: torch.Tensor, vec: torch.Tensor, alpha: float, token_mask: tor
                                _ptr(out))
     if rc != 0:
         raise ValueError(f"hook_oracle_steer rejected its arguments (code {rc})")
+    return out
+
+
+def residual_steer(hidden: torch.Tensor, delta: torch.Tensor, vec: torch.Tensor, alpha: float,
+                   token_mask: Optional[torch.Tensor]) -> torch.Tensor:
+    """hidden + delta (+ alpha * vec on masked rows), rounded once; returns a new tensor."""
+    lib = _load()
+    hidden, delta, vec = _cpu(hidden), _cpu(delta), _cpu(vec)
+    assert hidden.dtype in _DT and vec.dtype == hidden.dtype and delta.dtype == hidden.dtype
+    assert delta.shape == hidden.shape
+    mask = None if token_mask is None else _cpu(token_mask, torch.uint8)
+    T, D = hidden.shape
+    out = torch.empty_like(hidden)
+    rc = lib.hook_oracle_residual_steer(_ptr(hidden), _ptr(delta), _ptr(vec), float(alpha),
+                                        None if mask is None else _ptr(mask), T, D, _DT[hidden.dtype], _ptr(out))
+    if rc != 0:
+        raise ValueError(f"hook_oracle_residual_steer rejected its arguments (code {rc})")
     return out
 
 

@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
            "hook_attn_probe_device_status",
-           "hook_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -107,6 +107,10 @@ def load_library() -> ctypes.CDLL:
         lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_capture_qk.restype = ctypes.c_int
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
+        lib.hook_residual_add_steer.restype = ctypes.c_int
+        lib.hook_residual_add_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                                ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                ctypes.c_void_p]
         lib.hook_reduce_mass.restype = ctypes.c_int
         lib.hook_reduce_mass.argtypes = [ctypes.POINTER(HookReduceArgs)]
         lib.hook_parse_layer_heads.restype = ctypes.c_int
@@ -224,6 +228,17 @@ def call_from_batch(b, probe: bool = True, **kw) -> AttnProbeCall:
     return AttnProbeCall(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
                          b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
                          b.key_spans, b.scale, **kw)
+
+
+def hook_residual_add_steer(hidden, delta, vec, alpha: float, token_mask=None, stream=None):
+    """hidden += delta (+ alpha * vec on masked rows), in place, one rounding."""
+    lib = load_library()
+    T, D = hidden.shape
+    st = lib.hook_residual_add_steer(_p(hidden), _p(delta), _p(vec), float(alpha), _p(token_mask), T, D,
+                                     _DT[hidden.dtype], _stream_handle(stream))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_residual_add_steer")
+    return hidden
 
 
 def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel,

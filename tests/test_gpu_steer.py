@@ -73,3 +73,43 @@ def test_c1_and_c5_steer():
     keep = s5.token_mask == 0
     assert int(keep.sum()) == 64 + 192
     assert torch.equal(bits(got)[keep], bits(s5.hidden)[keep])
+
+
+# ---- steering fused into the residual add ----
+
+@pytest.mark.parametrize("dtype,T,D", [(torch.bfloat16, 300, 4096), (torch.bfloat16, 17, 520), (torch.float32, 65, 512),
+                                       (torch.float32, 9, 36)])
+def test_residual_steer_matches_oracle(dtype, T, D):
+    from paper_2603_06588_amd import binding
+    s = W.steer_batch(300 + T, T, D, dtype, alpha=3.25, mask_frac=0.6)
+    gen = torch.Generator().manual_seed(77 + T)
+    delta = (torch.randn((T, D), generator=gen) * 2).to(dtype)
+    delta[1] = (-s.hidden[1].double()).to(dtype)        # exact cancellation of h + d on one row
+    want = oracle.residual_steer(s.hidden, delta, s.vec, s.alpha, s.token_mask)
+    d = s.to(DEV)
+    binding.hook_residual_add_steer(d.hidden, delta.to(DEV), d.vec, d.alpha, d.token_mask)
+    torch.cuda.synchronize()
+    got = d.hidden.cpu()
+    assert _ulp_diff(got, want) <= 1
+    # the kernel adds the same three fp64 terms in the same order, so in practice every bit agrees
+    assert int((bits(got) != bits(want)).sum()) == 0
+    # plain residual add: null mask, and alpha = 0
+    want0 = oracle.residual_steer(s.hidden, delta, s.vec, 0.0, None)
+    for alpha, mask in ((3.0, None), (0.0, s.token_mask.to(DEV))):
+        h = s.hidden.to(DEV).clone()
+        binding.hook_residual_add_steer(h, delta.to(DEV), d.vec, alpha, mask)
+        torch.cuda.synchronize()
+        assert torch.equal(bits(h.cpu()), bits(want0))
+
+
+def test_residual_steer_c5_shape_sampled():
+    from paper_2603_06588_amd import binding
+    _, s = W.c5_mixed()
+    gen = torch.Generator().manual_seed(5)
+    delta = torch.randn(s.hidden.shape, generator=gen).to(s.hidden.dtype)
+    rows = torch.cat([torch.arange(0, 70), torch.arange(8250, 8448), torch.randint(70, 8250, (64,), generator=gen)])
+    want = oracle.residual_steer(s.hidden[rows], delta[rows], s.vec, s.alpha, s.token_mask[rows])
+    d = s.to(DEV)
+    binding.hook_residual_add_steer(d.hidden, delta.to(DEV), d.vec, d.alpha, d.token_mask)
+    torch.cuda.synchronize()
+    assert _ulp_diff(d.hidden.cpu()[rows], want) <= 1

@@ -438,3 +438,39 @@ def test_capture_reference_against_slicing():
         want = b.q[cu[i]:cu[i + 1]][rows][:, b.probe_heads.long()].permute(1, 0, 2)
         assert torch.equal(q_out[i, :, :len(rows)].view(torch.int16), want.view(torch.int16))
         assert (q_out[i, :, len(rows):] == 0).all()
+
+
+# --------------------------------------------------------------------------
+# steering fused into the residual add
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_residual_steer_exact_rational_and_identities(dtype):
+    s = W.steer_batch(83, 6, 16, dtype, alpha=-2.3, mask_frac=0.5)
+    s.token_mask[:] = torch.tensor([1, 0, 1, 1, 0, 1], dtype=torch.uint8)
+    gen = torch.Generator().manual_seed(84)
+    delta = (torch.randn((6, 16), generator=gen) * 3).to(dtype)
+    delta[2] = (-s.hidden[2].double()).to(dtype)            # cancellation: h + d = 0 exactly on row 2
+    out = oracle.residual_steer(s.hidden, delta, s.vec, s.alpha, s.token_mask)
+    alpha = Fraction(float(np.float32(s.alpha)))
+    for t in range(6):
+        for c in range(16):
+            exact = Fraction(float(s.hidden[t, c])) + Fraction(float(delta[t, c]))
+            if s.token_mask[t]:
+                exact += alpha * Fraction(float(s.vec[c]))
+            if dtype == torch.bfloat16:
+                assert (int(out[t, c].view(torch.int16)) & 0xFFFF) == _nearest_bf16_exact(exact)
+            else:
+                got = float(out[t, c])
+                near = np.float32(float(exact))
+                nb = [near, np.nextafter(near, np.float32(np.inf)), np.nextafter(near, np.float32(-np.inf))]
+                best = min(nb, key=lambda z: abs(Fraction(float(z)) - exact))
+                assert abs(Fraction(got) - exact) <= abs(Fraction(float(best)) - exact)
+    # delta = 0 reduces to plain steering; no mask / alpha = 0 reduce to a plain add
+    zero = torch.zeros_like(delta)
+    assert torch.equal(oracle.residual_steer(s.hidden, zero, s.vec, s.alpha, s.token_mask).view(torch.uint8),
+                       oracle.steer(s.hidden, s.vec, s.alpha, s.token_mask).view(torch.uint8))
+    plain = oracle.residual_steer(s.hidden, delta, s.vec, 0.0, s.token_mask)
+    assert torch.equal(plain, oracle.residual_steer(s.hidden, delta, s.vec, 5.0, None))
+    if dtype == torch.float32:
+        assert torch.equal(plain, (s.hidden.double() + delta.double()).float())
