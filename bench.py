@@ -123,7 +123,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5 (default: all)")
+    ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5,c6 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
                     help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON. "
@@ -145,7 +145,7 @@ def main() -> int:
         return 2
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(x for x in args.only.split(",") if x) or {"c2", "c3", "c4", "c5"}
+    only = set(x for x in args.only.split(",") if x) or {"c2", "c3", "c4", "c5", "c6"}
     if args.profile_workload:
         wl = args.profile_workload
         steer = None
@@ -359,6 +359,24 @@ def main() -> int:
                 "value": (dt_a + dt_s) * 1e3, "unit": "ms per step", "cores": oracle.num_threads(),
                 "kind": "oracle", "sample": f"c5_mixed whole: attention {dt_a:.2f} s, steering {dt_s:.3f} s",
                 "steer_gbs": steer_bytes / dt_s / 1e9}
+
+    if "c6" in only:
+        # re-ranking shape: one span per document, question rows selected; the probe is its own pass
+        b6 = W.c6_reranker(device=dev)
+        call6 = binding.call_from_batch(b6, probe=False)
+        mass6 = binding.hook_span_mass_batch(b6)
+        t6a = time_call(call6.launch, max(5, K // 5), 2)
+        t6p = time_call(lambda: binding.hook_span_mass_batch(b6, mass=mass6), K, Wm)
+        # keys the probe pass touches: pass 1 reads [0, L) once per (probed head, 16-row block),
+        # pass 2 the keys inside the spans once more
+        extra["reranker_c6"] = {
+            "workload": "c6_reranker: 4 prompts, 40-100 documents each, 32 question rows, 8 heads",
+            "total_q": b6.total_q, "spans": b6.max_spans,
+            "attention_ms": t6a["mean_ms"], "span_mass_ms": t6p["mean_ms"],
+            "span_mass_overhead_pct": 100.0 * t6p["mean_ms"] / t6a["mean_ms"],
+            "attention_tflops": attn_flops(b6) / (t6a["mean_ms"] * 1e-3) / 1e12}
+        del b6, call6, mass6
+        torch.cuda.empty_cache()
 
     line = {
         "metric": "hooked_attn_prefill_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,

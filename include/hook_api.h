@@ -56,7 +56,8 @@ typedef enum {
 
 typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
 
-#define HOOK_MAX_SPANS 8      /* S: key spans per sequence */
+#define HOOK_MAX_SPANS 8      /* S: key spans per sequence (hook_attn_probe) */
+#define HOOK_MAX_SPANS_WIDE 1024  /* S for hook_span_mass and hook_reduce_mass */
 #define HOOK_MAX_SEL_Q 4096   /* NQ: selected query rows per sequence */
 #define HOOK_BLOCK_SIZE 16    /* tokens per KV-cache block */
 
@@ -240,6 +241,24 @@ typedef struct hook_capture_qk_args {
 } hook_capture_qk_args;
 
 hook_status hook_capture_qk(const hook_capture_qk_args* args);
+
+/*
+ * Attention mass for many spans: the re-ranking shape of Section 3 (selective attention-based
+ * retrieval: attention from the query tokens of selected heads onto each document gives the
+ * document's relevance), i.e. tens to hundreds of spans x many query rows x a few heads.
+ * Takes the SAME argument struct as hook_attn_probe and writes the same
+ *   mass[i, p, t - query_sel[i,0], r]
+ * (identical definition, clipping and zero fill), but
+ *   - max_spans may be up to HOOK_MAX_SPANS_WIDE,
+ *   - no attention output is computed: out, v_cache, workspace and workspace_bytes are ignored
+ *     (run hook_attn_probe with num_probe_heads = 0 for the output),
+ *   - only HOOK_BF16 inputs are supported (HOOK_ERR_UNSUPPORTED otherwise).
+ * Two passes over the keys of each (sequence, probed head, 16-row block): exact softmax maximum
+ * and normaliser first, then the span sums; no atomics, results reproducible bit for bit.
+ * A content-free calibration prompt is a second call; hook_reduce_mass with negated weights
+ * subtracts it.
+ */
+hook_status hook_span_mass(const hook_attn_probe_args* args);
 
 /*
  * Score reductions over the mass tensor of one hook_attn_probe call (Section 2.2, analyzer:

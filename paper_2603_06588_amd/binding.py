@@ -20,7 +20,7 @@ HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
-           "hook_attn_probe_device_status",
+           "hook_attn_probe_device_status", "hook_span_mass",
            "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_capture_qk.restype = ctypes.c_int
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
+        lib.hook_span_mass.restype = ctypes.c_int
+        lib.hook_span_mass.argtypes = [ctypes.POINTER(HookAttnProbeArgs)]
         lib.hook_residual_add_steer.restype = ctypes.c_int
         lib.hook_residual_add_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                                 ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -215,6 +217,39 @@ def hook_attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe
                          query_sel, max_spans, key_spans, scale)
     call.launch(stream)
     return call.out, call.mass
+
+
+def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel, max_spans,
+                   key_spans, scale: float = 0.0, mass=None, stream=None) -> torch.Tensor:
+    """mass [num_seqs, P, NQ, S] for up to HOOK_MAX_SPANS_WIDE spans; computes no attention output."""
+    lib = load_library()
+    total_q, Hq, d = q.shape
+    num_blocks, Hkv, B, _ = k_cache.shape
+    num_seqs, max_blocks = block_table.shape
+    P = int(probe_heads.numel())
+    if q.dtype not in _DT:
+        raise HookError(3, "hook_span_mass (dtype)")
+    if mass is None:
+        mass = torch.empty((num_seqs, P, int(max_sel_q), int(max_spans)), dtype=torch.float32, device=q.device)
+    a = HookAttnProbeArgs()
+    a.num_seqs, a.total_q, a.num_q_heads, a.num_kv_heads = num_seqs, total_q, Hq, Hkv
+    a.head_dim, a.block_size, a.max_blocks_per_seq, a.num_blocks = d, B, max_blocks, num_blocks
+    a.dtype, a.scale = _DT[q.dtype], float(scale)
+    a.q, a.k_cache = _p(q), _p(k_cache)
+    a.block_table, a.seq_lens, a.cu_q_lens = _p(block_table), _p(seq_lens), _p(cu_q_lens)
+    a.num_probe_heads, a.probe_heads = P, _p(probe_heads)
+    a.max_sel_q, a.query_sel = int(max_sel_q), _p(query_sel)
+    a.max_spans, a.key_spans = int(max_spans), _p(key_spans)
+    a.mass, a.stream = _p(mass), _stream_handle(stream)
+    st = lib.hook_span_mass(ctypes.byref(a))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_span_mass")
+    return mass
+
+
+def hook_span_mass_batch(b, stream=None, mass=None) -> torch.Tensor:
+    return hook_span_mass(b.q, b.k_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads, b.max_sel_q,
+                          b.query_sel, b.max_spans, b.key_spans, b.scale, mass, stream)
 
 
 def hook_attn_probe_batch(b, stream=None, probe: bool = True):

@@ -39,24 +39,26 @@ __global__ __launch_bounds__(256) void k_reduce_mass(const ReduceParams p) {
   const int skip = (p.query_sel && p.query_sel[2 * i] < 0) ? min(-p.query_sel[2 * i], p.NQ) : 0;
   const int npairs = p.P * nv;
   if (p.mode == HOOK_REDUCE_SPAN_MEAN) {
-    float acc[kMaxSpans];
+    for (int r0 = 0; r0 < p.S; r0 += kMaxSpans) {   // kMaxSpans spans at a time in registers
+      float acc[kMaxSpans];
 #pragma unroll
-    for (int r = 0; r < kMaxSpans; ++r) acc[r] = 0.0f;
-    for (int e = lane; e < npairs; e += 64) {
-      const int ph = e / nv, t = skip + e - ph * nv;
-      const float wp = p.w ? p.w[ph] : 1.0f / (float)p.P;
-      const float* row = m + ((size_t)ph * p.NQ + t) * p.S;
+      for (int r = 0; r < kMaxSpans; ++r) acc[r] = 0.0f;
+      for (int e = lane; e < npairs; e += 64) {
+        const int ph = e / nv, t = skip + e - ph * nv;
+        const float wp = p.w ? p.w[ph] : 1.0f / (float)p.P;
+        const float* row = m + ((size_t)ph * p.NQ + t) * p.S + r0;
 #pragma unroll
-      for (int r = 0; r < kMaxSpans; ++r)
-        if (r < p.S) acc[r] += wp * row[r];
-    }
+        for (int r = 0; r < kMaxSpans; ++r)
+          if (r0 + r < p.S) acc[r] += wp * row[r];
+      }
 #pragma unroll
-    for (int r = 0; r < kMaxSpans; ++r) {
-      if (r < p.S) {
-        const float v = wave_sum(acc[r]) * inv_nv;
-        if (lane == 0) {
-          float* dst = p.scores + (size_t)i * p.S + r;
-          *dst = p.accumulate ? *dst + v : v;
+      for (int r = 0; r < kMaxSpans; ++r) {
+        if (r0 + r < p.S) {
+          const float v = wave_sum(acc[r]) * inv_nv;
+          if (lane == 0) {
+            float* dst = p.scores + (size_t)i * p.S + r0 + r;
+            *dst = p.accumulate ? *dst + v : v;
+          }
         }
       }
     }
@@ -95,7 +97,7 @@ extern "C" hook_status hook_reduce_mass(const hook_reduce_args* a) {
   using namespace hook;
   if (!a) return HOOK_ERR_NULL;
   if (a->num_seqs < 0 || a->num_probe_heads < 1 || a->max_sel_q < 1 || a->max_sel_q > HOOK_MAX_SEL_Q ||
-      a->max_spans < 1 || a->max_spans > HOOK_MAX_SPANS)
+      a->max_spans < 1 || a->max_spans > HOOK_MAX_SPANS_WIDE)
     return HOOK_ERR_SHAPE;
   if (a->mode != HOOK_REDUCE_SPAN_MEAN && a->mode != HOOK_REDUCE_RATIO_MEAN && a->mode != HOOK_REDUCE_RATIO_OF_SUMS)
     return HOOK_ERR_UNSUPPORTED;

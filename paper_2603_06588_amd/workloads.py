@@ -331,6 +331,32 @@ def c5_mixed(device="cpu", peaked: bool = False, shrink: int = 1,
     return b, SteerBatch("c5_steer", hidden, vec, 8.0, mask.to(device))
 
 
+def c6_reranker(device="cpu", peaked: bool = False, shrink: int = 1, num_prompts: int = 4) -> AttnBatch:
+    """Re-ranking prompts: a 64-token preamble, 40..100 documents of 64..256 tokens, a 32-token
+    question; one span per document, the question rows selected, 8 probed heads; 32 q / 8 kv
+    heads, d 128, bf16, seed 5.  Fresh prefill (L = n).  Spans beyond a prompt's document count
+    are empty."""
+    gen = torch.Generator().manual_seed(5)
+    lens, spans = [], []
+    for _ in range(num_prompts):
+        ndoc = max(2, _randint(40, 100, 1, gen)[0] // shrink)
+        pos = max(1, 64 // shrink)
+        sp = []
+        for dl in _randint(64, 256, ndoc, gen):
+            dl = max(1, dl // shrink)
+            sp.append((pos, pos + dl))
+            pos += dl
+        spans.append(sp)
+        lens.append(pos + 32)
+    nblk = sum((L + BLOCK_SIZE - 1) // BLOCK_SIZE for L in lens)
+    perm = torch.randperm(max(1, int(math.ceil(nblk * 1.25))), generator=gen)
+    heads = _distinct_heads(8, 32, gen)
+    qsel = [(L - 32, L) for L in lens]
+    std = 1.0 if peaked else 128 ** -0.5
+    return build_paged("c6_reranker" + ("_peaked" if peaked else ""), lens, lens, 32, 8, 128, torch.bfloat16, std,
+                       gen, heads, qsel, spans, max_sel_q=32, device=device, seed=5, block_perm=perm)
+
+
 def random_batch(
     seed: int,
     seq_lens: Sequence[int],

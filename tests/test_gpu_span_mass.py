@@ -1,0 +1,88 @@
+"""hook_span_mass (many spans, probe only) against the fp64 oracle (needs an MI355X)."""
+import pytest
+import torch
+
+import oracle
+from paper_2603_06588_amd import workloads as W
+from helpers import MASS_ATOL as MASS_TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _selected_rows(b):
+    rows = []
+    cu = b.cu_q_lens.tolist()
+    for i in range(b.num_seqs):
+        qb, qe = b.query_sel[i].tolist()
+        n = cu[i + 1] - cu[i]
+        rows += [cu[i] + t for t in range(max(qb, 0), min(qe, n, qb + b.max_sel_q))]
+    return rows
+
+
+def _check(b):
+    from paper_2603_06588_amd import binding
+    _, want = oracle.attn_probe_batch(b, rows=_selected_rows(b))
+    bd = b.to(DEV)
+    got = binding.hook_span_mass_batch(bd)
+    torch.cuda.synchronize()
+    again = binding.hook_span_mass_batch(bd)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)                                   # reproducible bit for bit
+    got = got.cpu().double()
+    assert torch.isfinite(got).all()
+    err = (got - want).abs().max().item()
+    assert err <= MASS_TOL, err
+    return got, want
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_span_mass_small_ragged(d):
+    # 40 spans incl. overlapping, empty, clipped and out-of-range ones; rows straddle 16-row blocks;
+    # a decode row, a chunk with prior context, an empty sequence, an empty selection
+    lens, qlens = [333, 90, 64, 1000, 17], [333, 1, 0, 40, 17]
+    b = W.random_batch(500 + d, lens, qlens, 8, 2, d, torch.bfloat16, std=1.0, num_probe_heads=3, max_sel_q=37,
+                       max_spans=40)
+    b.query_sel[4, 0], b.query_sel[4, 1] = 5, 5
+    got, want = _check(b)
+    assert want.abs().max() > 0.05
+
+
+def test_span_mass_agrees_with_probe_kernels_on_few_spans():
+    from paper_2603_06588_amd import binding
+    b = W.c2_prefill_8b(shrink=4, peaked=True).to(DEV)
+    _, m1 = binding.hook_attn_probe_batch(b)
+    m2 = binding.hook_span_mass_batch(b)
+    torch.cuda.synchronize()
+    assert (m1 - m2).abs().max().item() <= 2e-5
+
+
+@pytest.mark.parametrize("peaked", [False, True])
+def test_span_mass_reranker_shape(peaked):
+    b = W.c6_reranker(peaked=peaked, shrink=2)
+    got, want = _check(b)
+    # disjoint documents: the masses of one row cannot exceed 1 in total
+    assert got.sum(-1).max() <= 1 + 1e-4
+
+
+def test_span_mass_reranker_full_size_and_calibration():
+    from paper_2603_06588_amd import binding
+    from oracle.reduce import SPAN_MEAN, reduce_mass
+    b = W.c6_reranker()
+    got, want = _check(b)
+    # document scores: mean over heads and question rows, minus a calibration pass (here: the
+    # same prompts with other question tokens), entirely on the device
+    bd = b.to(DEV)
+    mass = binding.hook_span_mass_batch(bd)
+    calib = b.to(DEV)
+    calib.q = torch.roll(bd.q, 7, dims=0).contiguous()
+    mass_c = binding.hook_span_mass_batch(calib)
+    scores = binding.hook_reduce_mass(mass, 0, query_sel=bd.query_sel, cu_q_lens=bd.cu_q_lens)
+    w = torch.full((b.probe_heads.numel(),), -1.0 / b.probe_heads.numel(), device=DEV)
+    binding.hook_reduce_mass(mass_c, 0, query_sel=bd.query_sel, cu_q_lens=bd.cu_q_lens, head_weights=w,
+                             scores=scores, accumulate=True)
+    torch.cuda.synchronize()
+    ref = reduce_mass(mass.cpu().numpy(), SPAN_MEAN, query_sel=b.query_sel.tolist(), cu_q_lens=b.cu_q_lens.tolist())
+    ref = ref - reduce_mass(mass_c.cpu().numpy(), SPAN_MEAN, query_sel=b.query_sel.tolist(),
+                            cu_q_lens=b.cu_q_lens.tolist())
+    assert abs(scores.cpu().double().numpy() - ref).max() <= 4e-6

@@ -58,6 +58,22 @@ def test_capture_struct_matches_header_field_order(binding):
     assert lib.hook_capture_qk(ctypes.byref(a)) == 1          # null arrays
 
 
+def test_span_mass_argument_checks(binding):
+    lib = binding.load_library()
+    assert lib.hook_span_mass(None) == 1
+    a = binding.HookAttnProbeArgs()
+    a.num_seqs, a.total_q, a.num_q_heads, a.num_kv_heads, a.head_dim = 1, 4, 8, 2, 128
+    a.block_size, a.max_blocks_per_seq, a.num_blocks, a.dtype = 16, 4, 4, 0
+    a.num_probe_heads, a.max_sel_q, a.max_spans = 2, 4, 1025
+    assert lib.hook_span_mass(ctypes.byref(a)) == 3            # more spans than HOOK_MAX_SPANS_WIDE
+    a.max_spans = 100
+    assert lib.hook_span_mass(ctypes.byref(a)) == 1            # null arrays
+    a.dtype = 1
+    assert lib.hook_span_mass(ctypes.byref(a)) == 3            # fp32 inputs are not supported here
+    a.dtype, a.num_probe_heads = 0, 0
+    assert lib.hook_span_mass(ctypes.byref(a)) == 2            # nothing to probe
+
+
 def test_reduce_struct_and_argument_checks(binding):
     header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
     body = header[header.index("typedef struct hook_reduce_args {"):header.index("} hook_reduce_args;")]
@@ -80,7 +96,7 @@ def test_reduce_struct_and_argument_checks(binding):
     assert lib.hook_reduce_mass(ctypes.byref(a)) == 2          # span index out of range
     a.span_b, a.mode = 1, 7
     assert lib.hook_reduce_mass(ctypes.byref(a)) == 3          # unknown mode
-    a.mode, a.max_spans = 0, 9
+    a.mode, a.max_spans = 0, 1025
     assert lib.hook_reduce_mass(ctypes.byref(a)) == 2          # more spans than the compiled bound
     a.max_spans, a.num_seqs = 2, 0
     assert lib.hook_reduce_mass(ctypes.byref(a)) == 0          # empty batch: nothing to do
