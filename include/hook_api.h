@@ -316,6 +316,21 @@ hook_status hook_reduce_mass(const hook_reduce_args* args);
 hook_status hook_parse_layer_heads(const char* text, int32_t* layers, int32_t* heads, int32_t capacity,
                                    int32_t* count);
 
+/*
+ * Host helper: reads the JSON configuration file of the hook (Section 2, config file example:
+ * "params"/"important_heads" lists the [layer, head] pairs to analyse, "hookq"/"hookq_mode"
+ * says whether the query of the last token or of all tokens is wanted).  Everything else in
+ * the document is skipped.  All pointers are HOST pointers.
+ *   text         NUL-terminated JSON text whose top level is an object
+ *   layers, heads, capacity, *count   as for hook_parse_layer_heads, pairs in file order
+ *   *hookq_mode  0 = "last_token", 1 = "all_tokens", -1 = key absent
+ * Returns HOOK_ERR_SHAPE for malformed JSON, a pair that is not two non-negative integers, or an
+ * unknown mode string; HOOK_ERR_WORKSPACE when the pairs do not fit.  query_sel of a call is
+ * [n_i - 1, n_i) for mode 0 and [0, n_i) for mode 1.
+ */
+hook_status hook_parse_config_json(const char* text, int32_t* layers, int32_t* heads, int32_t capacity,
+                                   int32_t* count, int32_t* hookq_mode);
+
 const char* hook_status_string(hook_status status);
 int hook_version(void);
 

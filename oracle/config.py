@@ -26,3 +26,27 @@ def parse_layer_heads(text: str) -> Dict[int, List[int]]:
             raise ValueError(f"bad entry {part!r}")
         out.setdefault(layer, []).extend(heads)
     return out
+
+
+def parse_config_json(text: str):
+    """Section 2 (config file example): ([(layer, head), ...] in file order, hookq_mode or None),
+    read with the standard json module."""
+    import json
+    doc = json.loads(text)
+    if not isinstance(doc, dict):
+        raise ValueError("top level must be an object")
+    pairs = []
+    params = doc.get("params")
+    if isinstance(params, dict) and "important_heads" in params:
+        for item in params["important_heads"]:
+            if (not isinstance(item, list) or len(item) != 2 or
+                    any(isinstance(x, bool) or not isinstance(x, int) or x < 0 for x in item)):
+                raise ValueError(f"bad pair {item!r}")
+            pairs.append((item[0], item[1]))
+    mode = None
+    hookq = doc.get("hookq")
+    if isinstance(hookq, dict) and "hookq_mode" in hookq:
+        mode = hookq["hookq_mode"]
+        if mode not in ("last_token", "all_tokens"):
+            raise ValueError(f"unknown hookq_mode {mode!r}")
+    return pairs, mode

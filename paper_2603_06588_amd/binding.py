@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
            "hook_attn_probe_device_status", "hook_span_mass",
-           "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -119,6 +119,10 @@ def load_library() -> ctypes.CDLL:
         lib.hook_parse_layer_heads.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32),
                                                ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
                                                ctypes.POINTER(ctypes.c_int32)]
+        lib.hook_parse_config_json.restype = ctypes.c_int
+        lib.hook_parse_config_json.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32),
+                                               ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+                                               ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         lib.hook_status_string.restype = ctypes.c_char_p
         lib.hook_status_string.argtypes = [ctypes.c_int]
         lib.hook_version.restype = ctypes.c_int
@@ -339,6 +343,22 @@ def parse_layer_heads(text: str):
     if st != HOOK_OK:
         raise HookError(st, "hook_parse_layer_heads")
     return [(int(layers[i]), int(heads[i])) for i in range(n)]
+
+
+def parse_config_json(text: str):
+    """JSON config text -> ([(layer, head), ...] in file order, hookq_mode or None)."""
+    lib = load_library()
+    count, mode = ctypes.c_int32(0), ctypes.c_int32(-1)
+    st = lib.hook_parse_config_json(text.encode(), None, None, 0, ctypes.byref(count), ctypes.byref(mode))
+    if st not in (HOOK_OK, 4):
+        raise HookError(st, "hook_parse_config_json")
+    n = int(count.value)
+    layers, heads = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
+    st = lib.hook_parse_config_json(text.encode(), layers, heads, n, ctypes.byref(count), ctypes.byref(mode))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_parse_config_json")
+    names = {0: "last_token", 1: "all_tokens"}
+    return [(int(layers[i]), int(heads[i])) for i in range(n)], names.get(int(mode.value))
 
 
 def probe_heads_for_layer(pairs, layer: int, device="cpu") -> torch.Tensor:

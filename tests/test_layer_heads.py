@@ -72,3 +72,71 @@ def test_probe_heads_for_layer(binding):
     assert binding.probe_heads_for_layer(pairs, 8).tolist() == [1, 13, 14, 15]
     assert binding.probe_heads_for_layer(pairs, 7).tolist() == [20]
     assert binding.probe_heads_for_layer(pairs, 9).numel() == 0
+
+
+# ---- JSON configuration file ----
+
+def _config_golden():
+    text = open(os.path.join(ROOT, "tests", "golden", "config_example.json")).read()
+    lines = [l for l in open(os.path.join(ROOT, "tests", "golden", "config_example_expected.txt")).read().splitlines()
+             if l and not l.startswith("#")]
+    return text, ref_parse(lines[0]), lines[1], int(lines[2])
+
+
+def test_reference_config_reader_matches_the_papers_example():
+    from oracle.config import parse_config_json
+    text, want_map, want_mode, want_n = _config_golden()
+    pairs, mode = parse_config_json(text)
+    assert len(pairs) == want_n and mode == want_mode
+    assert _as_dict(pairs) == want_map
+    assert pairs[0] == (6, 9) and pairs[-1] == (19, 1)
+    assert parse_config_json('{"params": {}, "x": [1, {"hookq_mode": "all_tokens"}]}') == ([], None)
+    assert parse_config_json('{"hookq": {"hookq_mode": "all_tokens"}}') == ([], "all_tokens")
+    for bad in ['[1]', '{"params": {"important_heads": [[1]]}}', '{"params": {"important_heads": [[1, -2]]}}',
+                '{"params": {"important_heads": [[1, 2.5]]}}', '{"hookq": {"hookq_mode": "first"}}']:
+        with pytest.raises(ValueError):
+            parse_config_json(bad)
+
+
+def test_library_config_reader_matches_reference(binding):
+    from oracle.config import parse_config_json
+    text, want_map, want_mode, want_n = _config_golden()
+    pairs, mode = binding.parse_config_json(text)
+    assert (pairs, mode) == parse_config_json(text)
+    assert len(pairs) == want_n and _as_dict(pairs) == want_map and mode == want_mode
+    rng = random.Random(1)
+
+    def junk(depth=0):
+        k = rng.randint(0, 6 if depth < 3 else 4)
+        if k == 0:
+            return rng.randint(-50, 50)
+        if k == 1:
+            return rng.choice([True, False, None, 1.5e-3, -2.25, 'a "quoted" str', "important_heads", ""])
+        if k == 2:
+            return rng.random() * 1e6
+        if k == 3:
+            return "x" * rng.randint(0, 5)
+        if k == 4:
+            return [rng.randint(0, 9) for _ in range(rng.randint(0, 4))]
+        if k == 5:
+            return [junk(depth + 1) for _ in range(rng.randint(0, 3))]
+        return {f"k{j}": junk(depth + 1) for j in range(rng.randint(0, 3))}
+
+    for _ in range(200):
+        doc = {f"top{j}": junk() for j in range(rng.randint(0, 3))}
+        if rng.random() < 0.8:
+            doc["params"] = {"other": junk(), "important_heads": [[rng.randint(0, 80), rng.randint(0, 127)]
+                                                                  for _ in range(rng.randint(0, 30))]}
+        if rng.random() < 0.7:
+            doc["hookq"] = {"hookq_mode": rng.choice(["last_token", "all_tokens"]), "more": junk()}
+        if rng.random() < 0.3:
+            doc["decoy"] = {"params": {"important_heads": [[1, 2]]}, "hookq": {"hookq_mode": "all_tokens"}}
+        items = list(doc.items())
+        rng.shuffle(items)
+        s = json.dumps(dict(items), indent=rng.choice([None, 0, 2]))
+        assert binding.parse_config_json(s) == parse_config_json(s), s
+    for bad in ['', '[1]', '{"a": }', '{"a": 1,}', '{"params": {"important_heads": [[1]]}}', '{"a": 1} x',
+                '{"params": {"important_heads": [[1, -2]]}}', '{"params": {"important_heads": [[1, 2.5]]}}',
+                '{"params": {"important_heads": [[1, 2], ]}}', '{"hookq": {"hookq_mode": "first"}}', '{"a": tru}']:
+        with pytest.raises(binding.HookError):
+            binding.parse_config_json(bad)
