@@ -73,13 +73,13 @@ __global__ __launch_bounds__(256) void k_capture_k(const CaptureParams p) {
         const long long r = src_row[ts];
         int g = p.kv_heads[c];
         g = ((unsigned)g < (unsigned)p.Hkv) ? g : 0;
-        if (r >= 0) v[u] = p.k_cache[(size_t)(r + (long long)g * kBlock) * rc + cc];
+        if (r >= 0) v[u] = load_stream16(&p.k_cache[(size_t)(r + (long long)g * kBlock) * rc + cc]);
       }
     }
 #pragma unroll
     for (int u = 0; u < kInFlight; ++u) {
       const int idx = base + u * 256;
-      if (idx < nchunks) dst[idx] = v[u];
+      if (idx < nchunks) store_stream16(&dst[idx], v[u]);
     }
   }
 }

@@ -122,14 +122,14 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok_k) v = *reinterpret_cast<const uint4*>(kb + (size_t)j * D + 32 * s + 8 * kq);
+      if (ok_k) v = load_stream16(kb + (size_t)j * D + 32 * s + 8 * kq);
       kd[s] = v;
     }
 #pragma unroll
     for (int i = 0; i < C::KPL; ++i) {
       const int kl = C::KPL * vk + i;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (jb * kBlock + kl < kend) v = *reinterpret_cast<const uint4*>(vb + (size_t)kl * D + 8 * ch);
+      if (jb * kBlock + kl < kend) v = load_stream16(vb + (size_t)kl * D + 8 * ch);
       vd[i] = v;
     }
   };

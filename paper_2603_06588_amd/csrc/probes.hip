@@ -2,8 +2,8 @@
 //   k_probe_mfma  every SIMD issues independent 32x32x16 bf16 MFMAs back to back (two waves
 //                 per SIMD, four accumulators each) - the sustained matrix-core rate, which
 //                 sits below the nominal peak because the clock drops under this load;
-//   k_probe_read  a plain streaming read of a buffer with 16-byte loads - the sustained HBM
-//                 read bandwidth.
+//   k_probe_read  a streaming read of a buffer with 16-byte non-temporal loads - the sustained
+//                 HBM read bandwidth.
 #include "../../include/hook_api.h"
 #include "hook_device.h"
 
@@ -45,15 +45,24 @@ __global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, float* sink) {
   if (s == 12345.678f) sink[0] = s;   // keeps the loop alive
 }
 
+// Each workgroup takes contiguous 32 KB pieces round-robin and every thread keeps eight 16-byte
+// non-temporal loads in flight: of the patterns tried (grid-stride or contiguous pieces, plain
+// or non-temporal loads, 4 to 16 loads in flight) this one reads fastest on this chip.
+constexpr int kReadInFlight = 8;
+
 __global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ src, size_t n16, unsigned* sink) {
-  const size_t stride = (size_t)gridDim.x * 256;
+  constexpr size_t kPiece = 256 * kReadInFlight;   // 16-byte units per piece
   unsigned acc = 0;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-    acc ^= v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+  const size_t npieces = n16 / kPiece;
+  for (size_t c = blockIdx.x; c < npieces; c += gridDim.x) {
+    const uint4* p = src + c * kPiece + threadIdx.x;
+    uint4 v[kReadInFlight];
+#pragma unroll
+    for (int u = 0; u < kReadInFlight; ++u) v[u] = load_stream16(&p[u * 256]);
+#pragma unroll
+    for (int u = 0; u < kReadInFlight; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
-  for (; i < n16; i += stride) {
+  for (size_t i = npieces * kPiece + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
     const uint4 v = src[i];
     acc ^= v.x ^ v.y ^ v.z ^ v.w;
   }
@@ -79,7 +88,7 @@ hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* si
 hook_status hook_probe_hbm_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return HOOK_ERR_NULL;
   if (bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15) != 0) return HOOK_ERR_SHAPE;
-  hipLaunchKernelGGL(hook::k_probe_read, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(hook::k_probe_read, dim3(256 * 32), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(src), bytes / 16, static_cast<unsigned*>(sink));
   return hipGetLastError() == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
 }

@@ -46,8 +46,8 @@ __global__ __launch_bounds__(256) void k_residual_steer_bf16(uint4* __restrict__
 #pragma unroll
     for (int r = 0; r < kRowsPerWg; ++r)
       if (row0 + r < T) {
-        h[r] = hidden[(size_t)(row0 + r) * D8 + c];
-        d[r] = delta[(size_t)(row0 + r) * D8 + c];
+        h[r] = load_stream16(&hidden[(size_t)(row0 + r) * D8 + c]);
+        d[r] = load_stream16(&delta[(size_t)(row0 + r) * D8 + c]);
       }
     double av[8];
     if (any) {
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void k_residual_steer_bf16(uint4* __restrict__
         for (int k = 0; k < 4; ++k)
           y[k] = pack_bf16(bf16_lo(hw[k]) + bf16_lo(dw[k]), bf16_hi(hw[k]) + bf16_hi(dw[k]));
       }
-      hidden[(size_t)(row0 + r) * D8 + c] = make_uint4(y[0], y[1], y[2], y[3]);
+      store_stream16(&hidden[(size_t)(row0 + r) * D8 + c], make_uint4(y[0], y[1], y[2], y[3]));
     }
   }
 }
