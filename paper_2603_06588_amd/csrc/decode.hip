@@ -38,9 +38,10 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   const int kvh = bid % p.Hkv;
   const int rest = bid / p.Hkv;
   const int hg = rest % p.dec_hgroups;
-  const int item = rest / p.dec_hgroups;
-  const WorkItem it = p.dec_items[item];   // in bounds: the grid covers the item capacity
-  if (item >= p.hdr->n_decode) return;
+  const int turn = rest / p.dec_hgroups;
+  if (turn >= p.hdr->n_decode) return;
+  const int item = p.dec_order[turn];      // longest chunks are taken first
+  const WorkItem it = p.dec_items[item];
   const int seq = it.x, chunk = it.y, L = it.z, qrow = it.w;
   const int CH = p.hdr->chunk_keys;
   const int kstart = chunk * CH;

@@ -63,6 +63,7 @@ struct AttnParams {
   int pf_cap;
   WorkItem* dec_items;
   int dec_cap;
+  int* dec_order;                   // processing order of the decode items: longest chunks first
   int2* seq_dec;                    // per sequence {first decode item, number of chunks}
   float* partials;                  // [dec_cap, Hq, D + kPartialPad]
   // geometry chosen on the host from G

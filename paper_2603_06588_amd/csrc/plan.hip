@@ -5,8 +5,8 @@
 //   prefill items  one per (sequence with n_i >= 2, block of rows_per_wg query rows), ordered
 //                  by decreasing number of key tiles (longest first) with a counting sort;
 //   decode items   one per (sequence with n_i == 1, chunk of chunk_keys keys); the chunk size
-//                  (256..2048) is the largest that still gives the decode grid enough workgroups
-//                  to fill the chip.
+//                  (256..8192) is the largest that still gives the decode grid enough workgroups
+//                  to fill the chip; they are processed longest first.
 // The same launch zero-fills `mass`.
 #include "hook_device.h"
 
@@ -16,6 +16,8 @@ namespace {
 
 constexpr int kPlanThreads = 1024;
 constexpr int kListCap = 1024;   // queued prefill sequences
+constexpr int kChunkSizes = 5;   // candidate decode chunk sizes: 512 << k keys
+constexpr int kDecBuckets = (512 << (kChunkSizes - 1)) / kBlock;   // longest decode chunk in cache blocks
 
 struct SeqInfo { int L, n, row0, kind; };  // kind: 0 skip, 1 prefill, 2 decode
 
@@ -45,13 +47,18 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
 
   __shared__ int hist[kPlanBuckets];
   __shared__ int scan[kPlanBuckets];
-  __shared__ int sh_cnt[5];     // decode chunk counts for 512 / 1024 / 2048 keys (unused slot), status in [3]
+  __shared__ int sh_cnt[kChunkSizes];   // number of decode chunks for each candidate size
+  __shared__ int sh_status;
   __shared__ int sh_dec_next;
+  __shared__ int sh_dec_total;   // decode items actually written
   __shared__ int sh_nlist;
   __shared__ int sh_list[kListCap];
+  __shared__ int dhist[kDecBuckets + 1];   // decode items by length in cache blocks (<= 2048 / 16)
 
   for (int b = tid; b < kPlanBuckets; b += kPlanThreads) hist[b] = 0;
-  if (tid < 5) sh_cnt[tid] = 0;
+  if (tid < kChunkSizes) sh_cnt[tid] = 0;
+  if (tid == 0) sh_status = 0;
+  if (tid <= kDecBuckets) dhist[tid] = 0;
   if (tid == 0) { sh_dec_next = 0; sh_nlist = 0; }
   __syncthreads();
 
@@ -63,7 +70,9 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   const int wave = tid >> 6, lane = tid & 63;
   constexpr int kWaves = kPlanThreads / 64;
   int status = 0;
-  int c512 = 0, c1024 = 0, c2048 = 0;
+  int cnt[kChunkSizes];
+#pragma unroll
+  for (int k = 0; k < kChunkSizes; ++k) cnt[k] = 0;
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
     const SeqInfo s = read_seq(p, i, &status);
     if (s.kind == 1) {
@@ -78,13 +87,15 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
         }
       }
     } else if (s.kind == 2) {
-      c512 += (s.L + 511) / 512;
-      c1024 += (s.L + 1023) / 1024;
-      c2048 += (s.L + 2047) / 2048;
+#pragma unroll
+      for (int k = 0; k < kChunkSizes; ++k) cnt[k] += (s.L + (512 << k) - 1) / (512 << k);
     }
   }
-  if (c512) { atomicAdd(&sh_cnt[0], c512); atomicAdd(&sh_cnt[1], c1024); atomicAdd(&sh_cnt[2], c2048); }
-  if (status) atomicOr(&sh_cnt[3], status);
+  if (cnt[0]) {
+#pragma unroll
+    for (int k = 0; k < kChunkSizes; ++k) atomicAdd(&sh_cnt[k], cnt[k]);
+  }
+  if (status) atomicOr(&sh_status, status);
   __syncthreads();
   const int nlist = min(sh_nlist, kListCap);
   for (int k = wave; k < nlist; k += kWaves) {
@@ -122,13 +133,14 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     const int rb = kPlanBuckets - 1 - b;  // position of bucket b in the reversed order
     hist[b] = scan[rb] - hist[b];         // exclusive start (hist[b] still holds the count)
   }
-  // chunk size: long chunks stream best, so take the largest candidate that still yields at
-  // least 2048 decode workgroups (8 per CU), else 256 keys
+  // chunk size: every workgroup pays a few microseconds of start-up and merge, so long chunks
+  // stream best; take the largest candidate that still yields at least 2048 decode workgroups
+  // (8 per CU), else 256 keys
   const int wg_per_item = p.Hkv * p.dec_hgroups;
   int chunk = 256;
-  if ((long long)sh_cnt[2] * wg_per_item >= 2048) chunk = 2048;
-  else if ((long long)sh_cnt[1] * wg_per_item >= 2048) chunk = 1024;
-  else if ((long long)sh_cnt[0] * wg_per_item >= 2048) chunk = 512;
+#pragma unroll
+  for (int k = 0; k < kChunkSizes; ++k)
+    if ((long long)sh_cnt[k] * wg_per_item >= 2048) chunk = 512 << k;
   __syncthreads();
 
   // pass 2: scatter
@@ -142,6 +154,9 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       if (base + nch <= p.dec_cap) {
         sd = make_int2(base, nch);
         for (int c = 0; c < nch; ++c) p.dec_items[base + c] = make_int4(i, c, s.L, s.row0);
+        // every chunk but the last is full
+        if (nch > 1) atomicAdd(&dhist[chunk / kBlock], nch - 1);
+        atomicAdd(&dhist[(s.L - (nch - 1) * chunk + kBlock - 1) / kBlock], 1);
       }
     }
     p.seq_dec[i] = sd;
@@ -174,11 +189,49 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     }
   }
   __syncthreads();
+  // processing order of the decode items: by decreasing length, so that the short last chunks
+  // of the sequences fill the end of the launch instead of being scattered through it
+  if (tid < 64) {   // exclusive offsets in descending bucket order: lanes take runs of buckets, then a wave scan
+    constexpr int kPer = (kDecBuckets + 1 + 63) / 64;
+    int loc[kPer];
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const int b = kDecBuckets - (tid * kPer + k);
+      loc[k] = b >= 0 ? dhist[b] : 0;
+      sum += loc[k];
+    }
+    int inc = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(inc, off);
+      if (tid >= off) inc += t;
+    }
+    int run = inc - sum;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const int b = kDecBuckets - (tid * kPer + k);
+      if (b >= 0) { dhist[b] = run; run += loc[k]; }
+    }
+    if (tid == 63) sh_dec_total = inc;
+  }
+  __syncthreads();
+  for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
+    const int2 sd = p.seq_dec[i];   // written by this same thread above
+    if (sd.y == 0) continue;
+    int dummy = 0;
+    const SeqInfo s = read_seq(p, i, &dummy);
+    for (int c = 0; c < sd.y; ++c) {
+      const int len = (c + 1 < sd.y) ? chunk : s.L - c * chunk;
+      p.dec_order[atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1)] = sd.x + c;
+    }
+  }
+  __syncthreads();
   if (tid == 0) {
     p.hdr->n_prefill = min(n_prefill, p.pf_cap);
-    p.hdr->n_decode = min(sh_dec_next, p.dec_cap);
+    p.hdr->n_decode = sh_dec_total;
     p.hdr->chunk_keys = chunk;
-    p.hdr->status = sh_cnt[3];
+    p.hdr->status = sh_status;
   }
 }
 
