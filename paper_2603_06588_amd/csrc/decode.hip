@@ -88,13 +88,17 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
     const int qb = p.query_sel[2 * seq], qe = p.query_sel[2 * seq + 1];
     any_probe = (qb <= 0 && qe > 0);
     if (any_probe) {
-      lane_probe = (j < HP) && find_probe_slot(p.probe_heads, p.P, head0 + j) >= 0;
+      // is head0 + h probed?  The list is read 64 entries at a time, one per lane, and matched
+      // with a ballot, so the answer costs one load instead of a search per head
+      for (int i0 = 0; i0 < p.P; i0 += 64) {
+        const int ph = (i0 + lane < p.P) ? p.probe_heads[i0 + lane] : -1;
 #pragma unroll
-      for (int s = 0; s < kMaxSpans; ++s)
-        if (s < p.S) {
-          sp_a[s] = max(p.key_spans[((size_t)seq * p.S + s) * 2], 0);
-          sp_b[s] = p.key_spans[((size_t)seq * p.S + s) * 2 + 1];
+        for (int h = 0; h < HP; ++h) {
+          const bool hit = __builtin_amdgcn_ballot_w64(ph == head0 + h) != 0;
+          if (j == h) lane_probe = lane_probe || hit;
         }
+      }
+      load_spans(p.key_spans, seq, p.S, sp_a, sp_b);
     }
   }
 

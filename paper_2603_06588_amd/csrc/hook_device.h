@@ -103,12 +103,31 @@ __device__ __forceinline__ void store_stream16(void* p, const uint4 v) {
   __builtin_nontemporal_store(x, static_cast<u32x4*>(p));
 }
 
-// Index of `head` in the strictly increasing list probe_heads[0..P), or -1.
+// Index of `head` in the strictly increasing list probe_heads[0..P), or -1: a binary search, so
+// the chain of dependent loads is log2(P) long (a list that is not increasing just fails to
+// find some heads).
 __device__ __forceinline__ int find_probe_slot(const int* probe_heads, int P, int head) {
-  int slot = -1;
-  for (int i = 0; i < P; ++i)
-    if (probe_heads[i] == head) slot = i;
-  return slot;
+  int lo = 0, hi = P;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (probe_heads[mid] < head) lo = mid + 1; else hi = mid;
+  }
+  return (lo < P && probe_heads[lo] == head) ? lo : -1;
+}
+
+// Spans of one sequence, all fetched before any is waited for (entries past S repeat the last
+// span and are never used).
+__device__ __forceinline__ void load_spans(const int* key_spans, int seq, int S, int (&sp_a)[kMaxSpans],
+                                           int (&sp_b)[kMaxSpans]) {
+  const int2* sp = reinterpret_cast<const int2*>(key_spans) + (size_t)seq * S;
+  int2 v[kMaxSpans];
+#pragma unroll
+  for (int s = 0; s < kMaxSpans; ++s) v[s] = sp[min(s, S - 1)];
+#pragma unroll
+  for (int s = 0; s < kMaxSpans; ++s) {
+    sp_a[s] = s < S ? max(v[s].x, 0) : 0;
+    sp_b[s] = s < S ? v[s].y : 0;
+  }
 }
 
 // launchers (defined next to their kernels); all return hipGetLastError() after the launch

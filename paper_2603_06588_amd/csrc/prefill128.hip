@@ -483,12 +483,7 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
     pslot = find_probe_slot(p.probe_heads, p.P, head);
     qsel_b = p.query_sel[2 * seq];
     qsel_e = min(p.query_sel[2 * seq + 1], qsel_b + p.NQ);
-#pragma unroll
-    for (int s = 0; s < kMaxSpans; ++s)
-      if (s < p.S) {
-        sp_a[s] = max(p.key_spans[((size_t)seq * p.S + s) * 2], 0);
-        sp_b[s] = p.key_spans[((size_t)seq * p.S + s) * 2 + 1];
-      }
+    load_spans(p.key_spans, seq, p.S, sp_a, sp_b);
   }
   const bool wave_probe = wave_active && pslot >= 0 && qsel_b < min(wrow0 + kWaveRows, n) && qsel_e > wrow0;
 
