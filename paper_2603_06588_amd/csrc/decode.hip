@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   const int hg = rest % p.dec_hgroups;
   const int turn = rest / p.dec_hgroups;
   if (turn >= p.hdr->n_decode) return;
-  const int item = p.dec_order[turn];      // longest chunks are taken first
+  // longest chunks are taken first; the clamp only matters if the planner's capacity bound were
+  // ever violated
+  const int item = min(max(p.dec_order[turn], 0), p.dec_cap - 1);
   const WorkItem it = p.dec_items[item];
   const int seq = it.x, chunk = it.y, L = it.z, qrow = it.w;
   const int CH = p.hdr->chunk_keys;

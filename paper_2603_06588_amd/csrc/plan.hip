@@ -73,8 +73,11 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   int cnt[kChunkSizes];
 #pragma unroll
   for (int k = 0; k < kChunkSizes; ++k) cnt[k] = 0;
+  SeqInfo my_s;               // the thread's first sequence, kept for the later passes
+  my_s.L = my_s.n = my_s.row0 = my_s.kind = 0;
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
     const SeqInfo s = read_seq(p, i, &status);
+    if (i == tid) my_s = s;
     if (s.kind == 1) {
       const int pos = atomicAdd(&sh_nlist, 1);
       if (pos < kListCap) {
@@ -91,9 +94,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       for (int k = 0; k < kChunkSizes; ++k) cnt[k] += (s.L + (512 << k) - 1) / (512 << k);
     }
   }
-  if (cnt[0]) {
+  // one atomic per wave and counter: lanes hitting one LDS address are served one at a time
 #pragma unroll
-    for (int k = 0; k < kChunkSizes; ++k) atomicAdd(&sh_cnt[k], cnt[k]);
+  for (int k = 0; k < kChunkSizes; ++k) {
+    int v = cnt[k];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    if (lane == 0 && v) atomicAdd(&sh_cnt[k], v);
   }
   if (status) atomicOr(&sh_status, status);
   __syncthreads();
@@ -143,10 +150,12 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     if ((long long)sh_cnt[k] * wg_per_item >= 2048) chunk = 512 << k;
   __syncthreads();
 
-  // pass 2: scatter
+  // pass 2: scatter.  What the ordering pass below needs about a thread's first sequence stays
+  // in registers (batches of up to kPlanThreads sequences never re-read anything).
+  int2 my_sd = make_int2(0, 0);
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
     int dummy = 0;
-    const SeqInfo s = read_seq(p, i, &dummy);
+    const SeqInfo s = (i == tid) ? my_s : read_seq(p, i, &dummy);
     int2 sd = make_int2(0, 0);
     if (s.kind == 2) {
       const int nch = (s.L + chunk - 1) / chunk;
@@ -160,6 +169,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       }
     }
     p.seq_dec[i] = sd;
+    if (i == tid) my_sd = sd;
   }
   auto scatter_rows = [&](int i, const SeqInfo& s, int first, int step) {
     for (int r0 = first * p.rows_per_wg; r0 < s.n; r0 += step * p.rows_per_wg) {
@@ -217,12 +227,16 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   }
   __syncthreads();
   for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
-    const int2 sd = p.seq_dec[i];   // written by this same thread above
-    if (sd.y == 0) continue;
-    int dummy = 0;
-    const SeqInfo s = read_seq(p, i, &dummy);
+    int2 sd = my_sd;
+    int L = my_s.L;
+    if (i != tid) {
+      sd = p.seq_dec[i];   // written by this same thread above
+      if (sd.y == 0) continue;
+      int dummy = 0;
+      L = read_seq(p, i, &dummy).L;
+    }
     for (int c = 0; c < sd.y; ++c) {
-      const int len = (c + 1 < sd.y) ? chunk : s.L - c * chunk;
+      const int len = (c + 1 < sd.y) ? chunk : L - c * chunk;
       p.dec_order[atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1)] = sd.x + c;
     }
   }
