@@ -56,6 +56,20 @@ typedef enum {
 
 typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
 
+/*
+ * Composition of a batch, as far as the caller knows it.  The library never reads the sequence
+ * lengths on the host, so without a hint every call launches both the kernel for query chunks
+ * (n_i >= 2) and the pair for single rows (n_i == 1), one of which may find nothing to do.
+ * With a hint the launches that cannot have work are left out (two of four for a prefill-only
+ * batch).  A sequence that contradicts the hint is NOT computed: its rows of `out` stay untouched,
+ * its `mass` entries are zero and bit 3 of the device status word is set.
+ */
+typedef enum hook_batch_kind {
+  HOOK_BATCH_MIXED = 0,         /* anything (default) */
+  HOOK_BATCH_PREFILL_ONLY = 1,  /* every n_i is 0 or >= 2 */
+  HOOK_BATCH_DECODE_ONLY = 2    /* every n_i is 0 or 1 */
+} hook_batch_kind;
+
 #define HOOK_MAX_SPANS 8      /* S: key spans per sequence (hook_attn_probe) */
 #define HOOK_MAX_SPANS_WIDE 1024  /* S for hook_span_mass and hook_reduce_mass */
 #define HOOK_MAX_SEL_Q 4096   /* NQ: selected query rows per sequence */
@@ -122,6 +136,9 @@ typedef struct hook_attn_probe_args {
   void*  workspace;
   size_t workspace_bytes;      /* >= hook_attn_probe_workspace_bytes(args) */
   void*  stream;               /* hipStream_t; null = the default stream */
+
+  /* what the caller knows about the batch (it built cu_q_lens on the host); 0 is always valid */
+  int32_t batch_kind;          /* hook_batch_kind */
 } hook_attn_probe_args;
 
 /*
@@ -154,7 +171,8 @@ hook_status hook_attn_probe_timed(const hook_attn_probe_args* args, float* kerne
  * Debug aid: copies the device-side status word of the last hook_attn_probe
  * call that used `workspace` back to the host (this SYNCHRONISES the stream).
  * *status_bits: bit 0 = some n_i > L_i (sequence skipped), bit 1 = some L_i
- * exceeded max_blocks_per_seq * B (clamped), bit 2 = negative length.
+ * exceeded max_blocks_per_seq * B (clamped), bit 2 = negative length, bit 3 = a sequence
+ * contradicted batch_kind (not computed).
  */
 hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits);
 

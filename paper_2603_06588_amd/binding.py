@@ -37,7 +37,7 @@ class HookAttnProbeArgs(ctypes.Structure):
         ("max_spans", ctypes.c_int32), ("key_spans", ctypes.c_void_p),
         ("out", ctypes.c_void_p), ("mass", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-        ("stream", ctypes.c_void_p),
+        ("stream", ctypes.c_void_p), ("batch_kind", ctypes.c_int32),
     ]
 
 
@@ -69,6 +69,7 @@ class HookReduceArgs(ctypes.Structure):
 
 
 REDUCE_SPAN_MEAN, REDUCE_RATIO_MEAN, REDUCE_RATIO_OF_SUMS = 0, 1, 2
+BATCH_MIXED, BATCH_PREFILL_ONLY, BATCH_DECODE_ONLY = 0, 1, 2
 
 
 class HookError(RuntimeError):
@@ -157,7 +158,7 @@ class AttnProbeCall:
 
     def __init__(self, q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
                  query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0, out=None, mass=None,
-                 workspace=None):
+                 workspace=None, batch_kind: int = 0):
         lib = load_library()
         if q.dtype not in _DT:
             raise HookError(3, "hook_attn_probe (dtype)")
@@ -185,6 +186,7 @@ class AttnProbeCall:
             workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
         self.workspace = workspace
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel()
+        a.batch_kind = int(batch_kind)
         self.args = a
         self.workspace_needed = need
         self._fn = lib.hook_attn_probe

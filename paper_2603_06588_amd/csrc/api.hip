@@ -75,6 +75,7 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
     return HOOK_ERR_SHAPE;
   if (a->num_q_heads % a->num_kv_heads != 0) return HOOK_ERR_SHAPE;
   if (!shapes_supported(a)) return HOOK_ERR_UNSUPPORTED;
+  if (a->batch_kind < HOOK_BATCH_MIXED || a->batch_kind > HOOK_BATCH_DECODE_ONLY) return HOOK_ERR_SHAPE;
   const int P = a->num_probe_heads;
   if (P < 0 || P > a->num_q_heads) return HOOK_ERR_SHAPE;
   if (P > 0) {
@@ -120,6 +121,7 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
   p.partials = reinterpret_cast<float*>(ws + l.off_part);
   p.hpw = l.hpw; p.rows_per_wg = l.rows_per_wg; p.hgroups = l.hgroups;
   p.dec_hp = l.dec_hp; p.dec_hgroups = l.dec_hgroups;
+  p.batch_kind = a->batch_kind;
 
   hipStream_t st = static_cast<hipStream_t>(a->stream);
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
@@ -131,9 +133,10 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
     return HOOK_OK;
   }
   if (launch_plan(p, st) != hipSuccess || !mark(1)) return HOOK_ERR_LAUNCH;
-  if (launch_prefill(p, a->head_dim, st) != hipSuccess || !mark(2)) return HOOK_ERR_LAUNCH;
-  if (launch_decode(p, a->head_dim, st) != hipSuccess || !mark(3)) return HOOK_ERR_LAUNCH;
-  if (launch_combine(p, a->head_dim, st) != hipSuccess || !mark(4)) return HOOK_ERR_LAUNCH;
+  const bool chunks = a->batch_kind != HOOK_BATCH_DECODE_ONLY, singles = a->batch_kind != HOOK_BATCH_PREFILL_ONLY;
+  if ((chunks && launch_prefill(p, a->head_dim, st) != hipSuccess) || !mark(2)) return HOOK_ERR_LAUNCH;
+  if ((singles && launch_decode(p, a->head_dim, st) != hipSuccess) || !mark(3)) return HOOK_ERR_LAUNCH;
+  if ((singles && launch_combine(p, a->head_dim, st) != hipSuccess) || !mark(4)) return HOOK_ERR_LAUNCH;
   return HOOK_OK;
 }
 
@@ -150,6 +153,9 @@ hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_m
     if (hipEventSynchronize(ev[4]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
     for (int i = 0; i < 4 && rc == HOOK_OK; ++i)
       if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
+    // kernels that the batch_kind hint left out took no time (two events in a row still differ)
+    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_DECODE_ONLY) kernel_ms[1] = 0.0f;
+    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY) kernel_ms[2] = kernel_ms[3] = 0.0f;
   } else {
     for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
   }

@@ -25,7 +25,7 @@ constexpr int kPlanBuckets = 2048;  // counting-sort buckets (tile counts) of th
 constexpr float kLazyTau = 8.0f;
 
 // Device-side status bits written by the plan kernel.
-enum : int { kStatQGtL = 1, kStatLenClamped = 2, kStatNegative = 4 };
+enum : int { kStatQGtL = 1, kStatLenClamped = 2, kStatNegative = 4, kStatHint = 8 };
 
 struct PlanHeader {
   int n_prefill;   // prefill work items (row blocks)
@@ -67,6 +67,7 @@ struct AttnParams {
   int2* seq_dec;                    // per sequence {first decode item, number of chunks}
   float* partials;                  // [dec_cap, Hq, D + kPartialPad]
   // geometry chosen on the host from G
+  int batch_kind;                   // 0 mixed, 1 no single-row sequences, 2 only single-row sequences
   int hpw;                          // q heads per prefill workgroup (4, 2 or 1)
   int rows_per_wg;                  // 32 * (4 / hpw)
   int hgroups;                      // G / hpw

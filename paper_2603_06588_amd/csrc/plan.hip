@@ -34,6 +34,11 @@ __device__ __forceinline__ SeqInfo read_seq(const AttnParams& p, int i, int* sta
   if (s.row0 < 0 || s.row0 + s.n > p.total_q) { *status |= kStatNegative; return s; }
   if (s.n == 0) return s;
   s.kind = (s.n == 1) ? 2 : 1;
+  // a sequence the caller's hint rules out: its kernels are not launched, so it is dropped here
+  if ((p.batch_kind == 1 && s.kind == 2) || (p.batch_kind == 2 && s.kind == 1)) {
+    *status |= kStatHint;
+    s.kind = 0;
+  }
   return s;
 }
 

@@ -263,3 +263,39 @@ def test_many_prefill_sequences_overflow_the_planner_queue():
     lens = [2 + (i % 5) for i in range(nseq)]
     b = W.random_batch(180, lens, lens, 4, 2, 128, torch.bfloat16, num_probe_heads=2, max_sel_q=2, max_spans=1)
     _check(b, label="planner_overflow")
+
+
+def test_batch_kind_hint():
+    """A correct hint changes nothing but the launches; a wrong one drops the contradicting
+    sequences (rows untouched, mass zero) and sets bit 3 of the status word."""
+    from paper_2603_06588_amd import binding
+    pre = W.random_batch(190, [300, 77, 150], [300, 2, 90], 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=3,
+                         max_spans=2).to(DEV)
+    dec = W.random_batch(191, [300, 77, 1500], [1, 1, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=1,
+                         max_spans=2).to(DEV)
+    for b, kind in ((pre, binding.BATCH_PREFILL_ONLY), (dec, binding.BATCH_DECODE_ONLY)):
+        ref_out, ref_mass = run_hip(b)
+        call = binding.call_from_batch(b, batch_kind=kind)
+        call.out.fill_(float("nan"))
+        call.launch()
+        torch.cuda.synchronize()
+        assert torch.equal(bits(call.out), bits(ref_out)) and torch.equal(bits(call.mass), bits(ref_mass))
+        assert call.device_status() == 0
+        ms = call.launch_timed()
+        assert ms[1 if kind == binding.BATCH_DECODE_ONLY else 2] == 0.0     # the other side was not launched
+    mixed = W.random_batch(192, [300, 77, 150, 40], [300, 1, 90, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=3,
+                           max_sel_q=3, max_spans=2).to(DEV)
+    ref_out, ref_mass = run_hip(mixed)
+    call = binding.call_from_batch(mixed, batch_kind=binding.BATCH_PREFILL_ONLY)
+    call.out.fill_(7.0)
+    call.launch()
+    torch.cuda.synchronize()
+    assert call.device_status() & 8
+    cu = mixed.cu_q_lens.tolist()
+    for i, n in enumerate([300, 1, 90, 1]):
+        rows = slice(cu[i], cu[i + 1])
+        if n == 1:
+            assert (call.out[rows] == 7.0).all() and (call.mass[i] == 0).all()
+        else:
+            assert torch.equal(bits(call.out[rows]), bits(ref_out[rows]))
+            assert torch.equal(bits(call.mass[i]), bits(ref_mass[i]))
