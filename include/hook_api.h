@@ -168,6 +168,13 @@ hook_status hook_attn_probe(const hook_attn_probe_args* args);
 hook_status hook_attn_probe_timed(const hook_attn_probe_args* args, float* kernel_ms);
 
 /*
+ * Same, `reps` (1..4096) calls queued back to back before anything is waited for; kernel_ms
+ * receives the MEAN duration of each kernel over the repetitions.  This is the steady state a
+ * kernel trace of a timing loop sees (a call timed on its own starts on an idle, cooler chip).
+ */
+hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* args, int32_t reps, float* kernel_ms);
+
+/*
  * Debug aid: copies the device-side status word of the last hook_attn_probe
  * call that used `workspace` back to the host (this SYNCHRONISES the stream).
  * *status_bits: bit 0 = some n_i > L_i (sequence skipped), bit 1 = some L_i

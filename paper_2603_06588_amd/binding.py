@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhook.so")
 HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
-EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed",
+EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
            "hook_attn_probe_device_status", "hook_span_mass",
            "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
@@ -95,6 +95,9 @@ def load_library() -> ctypes.CDLL:
         lib.hook_attn_probe.argtypes = [ap]
         lib.hook_attn_probe_timed.restype = ctypes.c_int
         lib.hook_attn_probe_timed.argtypes = [ap, ctypes.POINTER(ctypes.c_float)]
+        lib.hook_attn_probe_timed_n.restype = ctypes.c_int
+        lib.hook_attn_probe_timed_n.argtypes = [ctypes.POINTER(HookAttnProbeArgs), ctypes.c_int32,
+                                                ctypes.POINTER(ctypes.c_float)]
         lib.hook_attn_probe_device_status.restype = ctypes.c_int
         lib.hook_attn_probe_device_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
                                                       ctypes.POINTER(ctypes.c_int32)]
@@ -204,6 +207,15 @@ class AttnProbeCall:
         st = load_library().hook_attn_probe_timed(ctypes.byref(self.args), ms)
         if st != HOOK_OK:
             raise HookError(st, "hook_attn_probe_timed")
+        return [float(x) for x in ms]
+
+    def launch_timed_n(self, reps: int, stream=None):
+        """`reps` launches back to back; mean (plan, prefill, decode, combine) kernel times in ms."""
+        self.args.stream = _stream_handle(stream)
+        ms = (ctypes.c_float * 4)()
+        st = load_library().hook_attn_probe_timed_n(ctypes.byref(self.args), int(reps), ms)
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe_timed_n")
         return [float(x) for x in ms]
 
     def device_status(self, stream=None) -> int:

@@ -5,6 +5,7 @@
 #include "hook_device.h"
 
 #include <cmath>
+#include <vector>
 
 namespace {
 
@@ -160,6 +161,34 @@ hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_m
     for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
+}
+
+hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* a, int32_t reps, float* kernel_ms) {
+  if (!kernel_ms) return HOOK_ERR_NULL;
+  if (reps < 1 || reps > 4096) return HOOK_ERR_SHAPE;
+  for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
+  std::vector<hipEvent_t> ev((size_t)reps * 5, nullptr);
+  hook_status rc = HOOK_OK;
+  size_t made = 0;
+  for (; made < ev.size(); ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
+  // all repetitions are queued before anything is waited for, so the kernels run back to back
+  for (int r = 0; r < reps && rc == HOOK_OK; ++r) rc = run_attn_probe(a, &ev[(size_t)r * 5]);
+  if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
+    if (hipEventSynchronize(ev.back()) != hipSuccess) rc = HOOK_ERR_LAUNCH;
+    double sum[4] = {0, 0, 0, 0};
+    for (int r = 0; r < reps && rc == HOOK_OK; ++r)
+      for (int i = 0; i < 4; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev[(size_t)r * 5 + i], ev[(size_t)r * 5 + i + 1]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
+        sum[i] += ms;
+      }
+    for (int i = 0; i < 4; ++i) kernel_ms[i] = (float)(sum[i] / reps);
+    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_DECODE_ONLY) kernel_ms[1] = 0.0f;
+    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY) kernel_ms[2] = kernel_ms[3] = 0.0f;
+  }
+  for (size_t i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
 }
 
