@@ -86,3 +86,25 @@ def test_span_mass_reranker_full_size_and_calibration():
     ref = ref - reduce_mass(mass_c.cpu().numpy(), SPAN_MEAN, query_sel=b.query_sel.tolist(),
                             cu_q_lens=b.cu_q_lens.tolist())
     assert abs(scores.cpu().double().numpy() - ref).max() <= 4e-6
+
+
+def test_span_mass_with_invalid_device_contents_completes():
+    """Block ids, lengths, selections and spans that make no sense must not take the call outside
+    its buffers; the valid sequences still come out right."""
+    from paper_2603_06588_amd import binding
+    b = W.random_batch(520, [200, 300, 150, 90], [200, 1, 150, 1], 8, 2, 128, torch.bfloat16, std=1.0,
+                       num_probe_heads=3, max_sel_q=20, max_spans=12, poison=False)
+    _, want = oracle.attn_probe_batch(b, rows=_selected_rows(b))
+    bad = b.to(DEV)
+    bad.seq_lens = bad.seq_lens.clone()
+    bad.seq_lens[2] = 100                                   # n_i > L_i: skipped
+    bad.block_table = bad.block_table.clone()
+    bad.block_table[3] = 0x7FFFFFF0                         # out-of-range ids: clamped
+    bad.key_spans = bad.key_spans.clone()
+    bad.key_spans[1, 0, 0], bad.key_spans[1, 0, 1] = -2**31, 2**31 - 1
+    bad.key_spans[1, 1, 0], bad.key_spans[1, 1, 1] = 2**31 - 1, -2**31
+    got = binding.hook_span_mass_batch(bad).cpu().double()
+    assert torch.isfinite(got).all()
+    assert (got[0] - want[0]).abs().max() <= MASS_TOL
+    assert (got[2] == 0).all()
+    assert abs(float(got[1, 0, 0, 0]) - 1.0) <= MASS_TOL and float(got[1, 0, 0, 1]) == 0.0
