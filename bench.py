@@ -122,7 +122,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default="", help="comma list of c2,c3,c4,c5,c6 (default: all)")
+    ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5,c6 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
                     help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON. "
@@ -144,7 +144,7 @@ def main() -> int:
         return 2
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(x for x in args.only.split(",") if x) or {"c2", "c3", "c4", "c5", "c6"}
+    only = set(x for x in args.only.split(",") if x) or {"c1", "c2", "c3", "c4", "c5", "c6"}
     if args.profile_workload:
         wl = args.profile_workload
         steer = None
@@ -355,6 +355,22 @@ def main() -> int:
                 "value": (dt_a + dt_s) * 1e3, "unit": "ms per step", "cores": oracle.num_threads(),
                 "kind": "oracle", "sample": f"c5_mixed whole: attention {dt_a:.2f} s, steering {dt_s:.3f} s",
                 "steer_gbs": steer_bytes / dt_s / 1e9}
+
+    if "c1" in only:
+        # the small fp32 case: one launch of the full-precision kernel, and the oracle on the same batch
+        b1, s1 = W.c1_tiny_prefill(device=dev)
+        call1 = binding.call_from_batch(b1)
+        t1 = time_call(call1.launch, K, Wm)
+        extra["tiny_c1"] = {"workload": "c1_tiny_prefill (fp32, 256 tokens, 8 heads, d 64)", "ms_per_step": t1["mean_ms"],
+                            "gflops": attn_flops(b1) / (t1["mean_ms"] * 1e-3) / 1e9}
+        if not args.no_cpu_baseline:
+            b1c = b1.to("cpu")
+            t0 = time.perf_counter()
+            for _ in range(20):
+                oracle.attn_probe_batch(b1c)
+            dt = (time.perf_counter() - t0) / 20
+            extra["tiny_c1"]["cpu_baseline"] = {"value": dt * 1e3, "unit": "ms per step", "cores": oracle.num_threads(),
+                                                "kind": "oracle", "sample": "c1_tiny_prefill whole, mean of 20 runs"}
 
     if "c6" in only:
         # re-ranking shape: one span per document, question rows selected; the probe is its own pass
