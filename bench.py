@@ -130,7 +130,7 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         return 2
 
