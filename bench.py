@@ -335,6 +335,15 @@ def main() -> int:
             binding.hook_steer(hiddens[state["i"] % 4], s5.vec, s5.alpha, s5.token_mask)
             state["i"] += 1
 
+        # writing the step's new K/V rows into the paged cache (what the attention call expects to find)
+        k_new = torch.randn((b5.total_q, b5.num_kv_heads, b5.head_dim), device=dev).to(torch.bfloat16)
+        v_new = torch.randn_like(k_new)
+        tkw = time_call(lambda: binding.hook_kv_write(k_new, v_new, b5.block_table, b5.seq_lens, b5.cu_q_lens,
+                                                      b5.k_cache, b5.v_cache), K, Wm)
+        kw_bytes = 4.0 * k_new.numel() * k_new.element_size()       # K and V rows read once, written once
+        extra["mixed_c5"]["kv_write"] = {"ms": tkw["mean_ms"], "bytes": kw_bytes,
+                                         "gbs": kw_bytes / (tkw["mean_ms"] * 1e-3) / 1e9}
+        del k_new, v_new
         t5f = time_call(fused_step, K, Wm)
         t5u = time_call(unfused_step, K, Wm)
         fused_bytes = 3.0 * s5.hidden.numel() * s5.hidden.element_size()

@@ -268,6 +268,32 @@ typedef struct hook_capture_qk_args {
 hook_status hook_capture_qk(const hook_capture_qk_args* args);
 
 /*
+ * Writes the keys and values of the new tokens into the paged cache, which hook_attn_probe expects
+ * to find there (it takes no separate new-token K/V): for sequence i and chunk-local row t,
+ *   pos = L_i - n_i + t,
+ *   k_cache[block_table[i, pos / B], g, pos % B, :] = k_new[cu_q_lens[i] + t, g, :]   for every kv head g
+ * and likewise for v.  Pure data movement (bit-identical copies), asynchronous on `stream`.
+ * Sequences with n_i > L_i, negative lengths or rows outside [0, total_q) are skipped; a block id
+ * outside [0, num_blocks) or a position beyond max_blocks_per_seq * B drops that token's write
+ * (nothing outside the cache is ever written).  Two sequences must not own the same block.
+ *   k_new, v_new   [total_q, Hkv, d], dtype of the cache, device
+ */
+typedef struct hook_kv_write_args {
+  int32_t num_seqs, total_q, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks;
+  int32_t dtype;
+  const void*    k_new;
+  const void*    v_new;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  const int32_t* cu_q_lens;
+  void*          k_cache;
+  void*          v_cache;
+  void*          stream;
+} hook_kv_write_args;
+
+hook_status hook_kv_write(const hook_kv_write_args* args);
+
+/*
  * Attention mass for many spans: the re-ranking shape of Section 3 (selective attention-based
  * retrieval: attention from the query tokens of selected heads onto each document gives the
  * document's relevance), i.e. tens to hundreds of spans x many query rows x a few heads.

@@ -36,3 +36,25 @@ def capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_se
             for c, g in enumerate(kvh):
                 k_out[cu_k[i] + j, c] = k_cache[blk, g, j % B]
     return q_out, k_out, torch.tensor(cu_k, dtype=torch.int32)
+
+
+def kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache):
+    """Reference for writing the new tokens' K/V into the paged cache (the attention call expects
+    them there): returns updated copies of (k_cache, v_cache).  Row t of sequence i goes to position
+    L_i - n_i + t; plain loops, single-row copies."""
+    k_cache, v_cache = k_cache.cpu().clone(), v_cache.cpu().clone()
+    k_new, v_new = k_new.cpu(), v_new.cpu()
+    table = block_table.cpu().tolist()
+    lens = seq_lens.cpu().tolist()
+    cu = cu_q_lens.cpu().tolist()
+    B = k_cache.shape[2]
+    for i, L in enumerate(lens):
+        n = cu[i + 1] - cu[i]
+        if n > L:
+            continue
+        for t in range(n):
+            pos = L - n + t
+            blk = table[i][pos // B]
+            k_cache[blk, :, pos % B] = k_new[cu[i] + t]
+            v_cache[blk, :, pos % B] = v_new[cu[i] + t]
+    return k_cache, v_cache

@@ -21,7 +21,7 @@ HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
            "hook_attn_probe_device_status", "hook_span_mass",
-           "hook_steer", "hook_residual_add_steer", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -53,6 +53,17 @@ class HookCaptureQkArgs(ctypes.Structure):
         ("num_capture_kv_heads", ctypes.c_int32), ("capture_kv_heads", ctypes.c_void_p),
         ("cu_k_lens", ctypes.c_void_p), ("total_k", ctypes.c_int32),
         ("q_out", ctypes.c_void_p), ("k_out", ctypes.c_void_p), ("stream", ctypes.c_void_p),
+    ]
+
+
+class HookKvWriteArgs(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("total_q", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+        ("seq_lens", ctypes.c_void_p), ("cu_q_lens", ctypes.c_void_p),
+        ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p), ("stream", ctypes.c_void_p),
     ]
 
 
@@ -111,6 +122,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_capture_qk.restype = ctypes.c_int
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
+        lib.hook_kv_write.restype = ctypes.c_int
+        lib.hook_kv_write.argtypes = [ctypes.POINTER(HookKvWriteArgs)]
         lib.hook_span_mass.restype = ctypes.c_int
         lib.hook_span_mass.argtypes = [ctypes.POINTER(HookAttnProbeArgs)]
         lib.hook_residual_add_steer.restype = ctypes.c_int
@@ -292,6 +305,23 @@ def hook_residual_add_steer(hidden, delta, vec, alpha: float, token_mask=None, s
     if st != HOOK_OK:
         raise HookError(st, "hook_residual_add_steer")
     return hidden
+
+
+def hook_kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache, stream=None) -> None:
+    """Scatter the new tokens' K/V rows ([total_q, Hkv, d]) into the paged cache, in place."""
+    lib = load_library()
+    total_q, Hkv, d = k_new.shape
+    num_blocks, _, B, _ = k_cache.shape
+    num_seqs, max_blocks = block_table.shape
+    a = HookKvWriteArgs()
+    a.num_seqs, a.total_q, a.num_kv_heads, a.head_dim = num_seqs, total_q, Hkv, d
+    a.block_size, a.max_blocks_per_seq, a.num_blocks, a.dtype = B, max_blocks, num_blocks, _DT[k_new.dtype]
+    a.k_new, a.v_new, a.block_table = _p(k_new), _p(v_new), _p(block_table)
+    a.seq_lens, a.cu_q_lens = _p(seq_lens), _p(cu_q_lens)
+    a.k_cache, a.v_cache, a.stream = _p(k_cache), _p(v_cache), _stream_handle(stream)
+    st = lib.hook_kv_write(ctypes.byref(a))
+    if st != HOOK_OK:
+        raise HookError(st, "hook_kv_write")
 
 
 def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel,

@@ -63,3 +63,49 @@ def test_capture_with_invalid_device_contents_completes():
                                     cu_bad, 135)
     torch.cuda.synchronize()
     assert (k2[40:60] == 0).all()
+
+
+# ---- writing the new tokens' K/V into the paged cache ----
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_kv_write_matches_reference(dtype, d):
+    from oracle.capture import kv_write
+    from paper_2603_06588_amd import binding
+    b = W.random_batch(310, [333, 17, 64, 1000, 9], [100, 1, 64, 1, 0], 8, 2, d, dtype, num_probe_heads=1, max_sel_q=1,
+                       poison=False)
+    gen = torch.Generator().manual_seed(311)
+    k_new = torch.randn((b.total_q, 2, d), generator=gen).to(dtype)
+    v_new = torch.randn((b.total_q, 2, d), generator=gen).to(dtype)
+    want_k, want_v = kv_write(k_new, v_new, b.block_table, b.seq_lens, b.cu_q_lens, b.k_cache, b.v_cache)
+    bd = b.to(DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bd.seq_lens, bd.cu_q_lens, bd.k_cache,
+                          bd.v_cache)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(bd.k_cache.cpu()), bits(want_k)) and torch.equal(bits(bd.v_cache.cpu()), bits(want_v))
+
+
+def test_kv_write_then_attention_and_invalid_contents():
+    """The written cache feeds the attention call; nonsense ids and lengths drop writes, never fault."""
+    import oracle
+    from oracle.capture import kv_write
+    from paper_2603_06588_amd import binding
+    from helpers import compare_with_oracle
+    b = W.random_batch(312, [300, 150, 700], [300, 1, 20], 8, 2, 128, torch.bfloat16, std=1.0, num_probe_heads=2,
+                       max_sel_q=2, max_spans=2)
+    gen = torch.Generator().manual_seed(313)
+    k_new = torch.randn((b.total_q, 2, 128), generator=gen).to(torch.bfloat16)
+    v_new = torch.randn((b.total_q, 2, 128), generator=gen).to(torch.bfloat16)
+    bd = b.to(DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bd.seq_lens, bd.cu_q_lens, bd.k_cache,
+                          bd.v_cache)
+    out, mass = binding.hook_attn_probe_batch(bd)
+    torch.cuda.synchronize()
+    b.k_cache, b.v_cache = kv_write(k_new, v_new, b.block_table, b.seq_lens, b.cu_q_lens, b.k_cache, b.v_cache)
+    compare_with_oracle(b, out, mass, label="after kv_write")
+    before_k = bd.k_cache.clone()
+    bad_table = torch.full_like(bd.block_table, 0x7FFFFFF0)
+    bad_lens = torch.tensor([2**31 - 1, -5, 3], dtype=torch.int32, device=DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bad_table, bd.seq_lens, bd.cu_q_lens, bd.k_cache, bd.v_cache)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bad_lens, bd.cu_q_lens, bd.k_cache, bd.v_cache)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(bd.k_cache), bits(before_k))

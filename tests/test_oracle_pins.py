@@ -474,3 +474,25 @@ def test_residual_steer_exact_rational_and_identities(dtype):
     assert torch.equal(plain, oracle.residual_steer(s.hidden, delta, s.vec, 5.0, None))
     if dtype == torch.float32:
         assert torch.equal(plain, (s.hidden.double() + delta.double()).float())
+
+
+def test_kv_write_reference_round_trip():
+    """Writing the new rows and gathering them back through the block table returns them, and
+    nothing else in the cache moves (the attention oracle then sees exactly the written values)."""
+    from oracle.capture import capture_qk, kv_write
+    lens, qlens = [37, 64, 5, 20], [10, 64, 1, 0]
+    b = W.random_batch(92, lens, qlens, 8, 4, 16, torch.bfloat16, num_probe_heads=1, max_sel_q=1, poison=False)
+    gen = torch.Generator().manual_seed(93)
+    k_new = torch.randn((b.total_q, 4, 16), generator=gen).to(torch.bfloat16)
+    v_new = torch.randn((b.total_q, 4, 16), generator=gen).to(torch.bfloat16)
+    kc, vc = kv_write(k_new, v_new, b.block_table, b.seq_lens, b.cu_q_lens, b.k_cache, b.v_cache)
+    kvh = torch.arange(4, dtype=torch.int32)
+    _, k_all, cu_k = capture_qk(b.q, kc, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads, 1, b.query_sel, kvh)
+    _, k_old, _ = capture_qk(b.q, b.k_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads, 1, b.query_sel, kvh)
+    cu = b.cu_q_lens.tolist()
+    for i, (L, n) in enumerate(zip(lens, qlens)):
+        got = k_all[cu_k[i]:cu_k[i + 1]]
+        assert torch.equal(got[L - n:].view(torch.int16), k_new[cu[i]:cu[i + 1]].view(torch.int16))
+        assert torch.equal(got[:L - n].view(torch.int16), k_old[cu_k[i]:cu_k[i + 1]][:L - n].view(torch.int16))
+    changed = (kc.view(torch.int16) != b.k_cache.view(torch.int16)).any(-1).any(1).sum()     # (block, slot) pairs
+    assert int(changed) <= sum(qlens) and int((vc.view(torch.int16) != b.v_cache.view(torch.int16)).any(-1).any(1).sum()) <= sum(qlens)
