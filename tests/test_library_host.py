@@ -58,6 +58,30 @@ def test_capture_struct_matches_header_field_order(binding):
     assert lib.hook_capture_qk(ctypes.byref(a)) == 1          # null arrays
 
 
+def test_kv_write_struct_and_argument_checks(binding):
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    body = header[header.index("typedef struct hook_kv_write_args {"):header.index("} hook_kv_write_args;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for stmt in body.split("{", 1)[1].split(";"):
+        stmt = stmt.strip()
+        if not stmt:
+            continue
+        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
+        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    assert names == [f[0] for f in binding.HookKvWriteArgs._fields_]
+    lib = binding.load_library()
+    assert lib.hook_kv_write(None) == 1
+    a = binding.HookKvWriteArgs()
+    a.num_seqs, a.total_q, a.num_kv_heads, a.head_dim, a.block_size = 1, 4, 2, 128, 16
+    a.max_blocks_per_seq, a.num_blocks = 4, 4
+    assert lib.hook_kv_write(ctypes.byref(a)) == 1             # null arrays
+    a.block_size = 8
+    assert lib.hook_kv_write(ctypes.byref(a)) == 3             # block size
+    a.block_size, a.total_q = 16, 0
+    assert lib.hook_kv_write(ctypes.byref(a)) == 0             # nothing to write
+
+
 def test_span_mass_argument_checks(binding):
     lib = binding.load_library()
     assert lib.hook_span_mass(None) == 1
