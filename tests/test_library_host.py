@@ -17,6 +17,21 @@ def binding():
     return b
 
 
+def _header_struct_fields(struct_name: str):
+    """Field names of a struct declared in include/hook_api.h, in declaration order."""
+    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
+    body = header[header.index(f"typedef struct {struct_name} {{"):header.index(f"}} {struct_name};")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for stmt in body.split("{", 1)[1].split(";"):
+        stmt = stmt.strip()
+        if not stmt:
+            continue
+        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
+        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    return names
+
+
 def test_exports_every_declared_symbol(binding):
     header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
     declared = set(re.findall(r"\b(hook_[a-z0-9_]+)\s*\(", header))
@@ -29,23 +44,11 @@ def test_exports_every_declared_symbol(binding):
 
 
 def test_args_struct_matches_header_field_order(binding):
-    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
-    body = header[header.index("typedef struct hook_attn_probe_args {"):header.index("} hook_attn_probe_args;")]
-    fields = re.findall(r"^\s*(?:const\s+)?[a-z0-9_]+\*?\s+\*?\s*([a-z_]+);", body, flags=re.M)
-    assert fields == [f[0] for f in binding.HookAttnProbeArgs._fields_]
+    assert _header_struct_fields("hook_attn_probe_args") == [f[0] for f in binding.HookAttnProbeArgs._fields_]
 
 
 def test_capture_struct_matches_header_field_order(binding):
-    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
-    body = header[header.index("typedef struct hook_capture_qk_args {"):header.index("} hook_capture_qk_args;")]
-    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    names = []
-    for stmt in body.split("{", 1)[1].split(";"):
-        stmt = stmt.strip()
-        if not stmt:
-            continue
-        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
-        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    names = _header_struct_fields("hook_capture_qk_args")
     assert names == [f[0] for f in binding.HookCaptureQkArgs._fields_]
     lib = binding.load_library()
     a = binding.HookCaptureQkArgs()
@@ -59,16 +62,7 @@ def test_capture_struct_matches_header_field_order(binding):
 
 
 def test_kv_write_struct_and_argument_checks(binding):
-    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
-    body = header[header.index("typedef struct hook_kv_write_args {"):header.index("} hook_kv_write_args;")]
-    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    names = []
-    for stmt in body.split("{", 1)[1].split(";"):
-        stmt = stmt.strip()
-        if not stmt:
-            continue
-        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
-        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    names = _header_struct_fields("hook_kv_write_args")
     assert names == [f[0] for f in binding.HookKvWriteArgs._fields_]
     lib = binding.load_library()
     assert lib.hook_kv_write(None) == 1
@@ -99,16 +93,7 @@ def test_span_mass_argument_checks(binding):
 
 
 def test_reduce_struct_and_argument_checks(binding):
-    header = open(os.path.join(ROOT, "include", "hook_api.h")).read()
-    body = header[header.index("typedef struct hook_reduce_args {"):header.index("} hook_reduce_args;")]
-    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    names = []
-    for stmt in body.split("{", 1)[1].split(";"):
-        stmt = stmt.strip()
-        if not stmt:
-            continue
-        decl = stmt.split(None, 1)[1] if not stmt.startswith("const") else stmt.split(None, 2)[2]
-        names += [n.strip().lstrip("*").strip() for n in decl.split(",")]
+    names = _header_struct_fields("hook_reduce_args")
     assert names == [f[0] for f in binding.HookReduceArgs._fields_]
     lib = binding.load_library()
     assert lib.hook_reduce_mass(None) == 1
