@@ -386,14 +386,17 @@ def main() -> int:
         b6 = W.c6_reranker(device=dev)
         call6 = binding.call_from_batch(b6, probe=False)
         mass6 = binding.hook_span_mass_batch(b6)
+        ws6 = torch.empty(1 << 22, dtype=torch.uint8, device=dev)    # scratch for the split form (4 MB is plenty)
         t6a = time_call(call6.launch, max(5, K // 5), 2)
-        t6p = time_call(lambda: binding.hook_span_mass_batch(b6, mass=mass6), K, Wm)
+        t6p = time_call(lambda: binding.hook_span_mass_batch(b6, mass=mass6, workspace=ws6), K, Wm)
+        t6s = time_call(lambda: binding.hook_span_mass_batch(b6, mass=mass6, use_workspace=False), K, Wm)
         # keys the probe pass touches: pass 1 reads [0, L) once per (probed head, 16-row block),
         # pass 2 the keys inside the spans once more
         extra["reranker_c6"] = {
             "workload": "c6_reranker: 4 prompts, 40-100 documents each, 32 question rows, 8 heads",
             "total_q": b6.total_q, "spans": b6.max_spans,
             "attention_ms": t6a["mean_ms"], "span_mass_ms": t6p["mean_ms"],
+            "span_mass_without_scratch_ms": t6s["mean_ms"],
             "span_mass_overhead_pct": 100.0 * t6p["mean_ms"] / t6a["mean_ms"],
             "attention_tflops": attn_flops(b6) / (t6a["mean_ms"] * 1e-3) / 1e12}
         del b6, call6, mass6

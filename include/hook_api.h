@@ -301,8 +301,12 @@ hook_status hook_kv_write(const hook_kv_write_args* args);
  *   mass[i, p, t - query_sel[i,0], r]
  * (identical definition, clipping and zero fill), but
  *   - max_spans may be up to HOOK_MAX_SPANS_WIDE,
- *   - no attention output is computed: out, v_cache, workspace and workspace_bytes are ignored
- *     (run hook_attn_probe with num_probe_heads = 0 for the output),
+ *   - no attention output is computed: out and v_cache are ignored (run hook_attn_probe with
+ *     num_probe_heads = 0 for the output),
+ *   - workspace is optional scratch: with at least hook_span_mass_workspace_bytes(args) bytes (8-byte
+ *     aligned) the two passes run as two kernels split over keys and spans and use the whole chip;
+ *     without it one workgroup per (sequence, head, 16 rows) does everything (same results to
+ *     rounding, several times slower on long sequences),
  *   - only HOOK_BF16 inputs are supported (HOOK_ERR_UNSUPPORTED otherwise).
  * Two passes over the keys of each (sequence, probed head, 16-row block): exact softmax maximum
  * and normaliser first, then the span sums; no atomics, results reproducible bit for bit.
@@ -310,6 +314,9 @@ hook_status hook_kv_write(const hook_kv_write_args* args);
  * subtracts it.
  */
 hook_status hook_span_mass(const hook_attn_probe_args* args);
+
+/* Scratch bytes that let hook_span_mass take its split path (0: not available for these shapes). */
+size_t hook_span_mass_workspace_bytes(const hook_attn_probe_args* args);
 
 /*
  * Score reductions over the mass tensor of one hook_attn_probe call (Section 2.2, analyzer:

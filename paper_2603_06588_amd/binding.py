@@ -20,7 +20,7 @@ HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
-           "hook_attn_probe_device_status", "hook_span_mass",
+           "hook_attn_probe_device_status", "hook_span_mass", "hook_span_mass_workspace_bytes",
            "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
@@ -124,6 +124,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
         lib.hook_kv_write.restype = ctypes.c_int
         lib.hook_kv_write.argtypes = [ctypes.POINTER(HookKvWriteArgs)]
+        lib.hook_span_mass_workspace_bytes.restype = ctypes.c_size_t
+        lib.hook_span_mass_workspace_bytes.argtypes = [ctypes.POINTER(HookAttnProbeArgs)]
         lib.hook_span_mass.restype = ctypes.c_int
         lib.hook_span_mass.argtypes = [ctypes.POINTER(HookAttnProbeArgs)]
         lib.hook_residual_add_steer.restype = ctypes.c_int
@@ -251,8 +253,11 @@ def hook_attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe
 
 
 def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel, max_spans,
-                   key_spans, scale: float = 0.0, mass=None, stream=None) -> torch.Tensor:
-    """mass [num_seqs, P, NQ, S] for up to HOOK_MAX_SPANS_WIDE spans; computes no attention output."""
+                   key_spans, scale: float = 0.0, mass=None, stream=None, workspace=None,
+                   use_workspace: bool = True) -> torch.Tensor:
+    """mass [num_seqs, P, NQ, S] for up to HOOK_MAX_SPANS_WIDE spans; computes no attention output.
+    A scratch tensor lets the library split the work over the chip; it is allocated here unless
+    one is passed in or use_workspace is False."""
     lib = load_library()
     total_q, Hq, d = q.shape
     num_blocks, Hkv, B, _ = k_cache.shape
@@ -272,15 +277,20 @@ def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, ma
     a.max_sel_q, a.query_sel = int(max_sel_q), _p(query_sel)
     a.max_spans, a.key_spans = int(max_spans), _p(key_spans)
     a.mass, a.stream = _p(mass), _stream_handle(stream)
+    if workspace is None and use_workspace:
+        need = int(lib.hook_span_mass_workspace_bytes(ctypes.byref(a)))
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=q.device) if need else None
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = _p(workspace), workspace.numel()
     st = lib.hook_span_mass(ctypes.byref(a))
     if st != HOOK_OK:
         raise HookError(st, "hook_span_mass")
     return mass
 
 
-def hook_span_mass_batch(b, stream=None, mass=None) -> torch.Tensor:
+def hook_span_mass_batch(b, stream=None, mass=None, workspace=None, use_workspace: bool = True) -> torch.Tensor:
     return hook_span_mass(b.q, b.k_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads, b.max_sel_q,
-                          b.query_sel, b.max_spans, b.key_spans, b.scale, mass, stream)
+                          b.query_sel, b.max_spans, b.key_spans, b.scale, mass, stream, workspace, use_workspace)
 
 
 def hook_attn_probe_batch(b, stream=None, probe: bool = True):

@@ -3,7 +3,7 @@
 // then runs with probing switched off.
 //
 // Workgroup = (sequence, probed head, block of 16 selected rows), 16 waves.
-//   pass 1  the waves share the keys [0, pos_max] (64-key groups round-robin), each lane keeps a
+//   pass 1  the waves share the keys [0, pos_max] (32-key groups round-robin), each lane keeps a
 //           running (max, sum) for its row over the keys it sees; merged across lanes and waves
 //           into the exact softmax maximum and normaliser of each row;
 //   pass 2  the spans are dealt to the waves; a wave walks the keys of its span, recomputes the
@@ -21,7 +21,7 @@ namespace {
 
 constexpr int kSmWaves = 16;
 constexpr int kSmRows = 16;     // query rows per workgroup
-constexpr int kSmGroup = 4;     // 16-key tiles fetched together (independent loads in flight)
+constexpr int kSmGroup = 2;     // 16-key tiles per pipeline stage
 
 struct SpanParams {
   int num_seqs, total_q, Hq, Hkv, G, max_blocks, num_blocks;
@@ -38,6 +38,10 @@ struct SpanParams {
   int S;
   const int* key_spans;
   float* mass;
+  float2* stats;    // split path: (max, sum) of every (sequence, probed head, row slot, key split)
+  int nsplit;       // key splits of pass 1
+  int sgroups;      // span groups of pass 2
+  int nq_pad;       // NQ rounded up to whole 16-row blocks
 };
 
 template <int D>
@@ -50,14 +54,57 @@ struct Frag {
 // chunks 4 s + quarter of its key's row.  `key` is this lane's absolute key (already clamped
 // into the sequence), looked up through the block table.
 template <int D>
-__device__ __forceinline__ void load_keys(const SpanParams& p, const int* bt, int g, int key, int quarter,
-                                          Frag<D>& f) {
-  int blk = bt[key >> 4];
+__device__ __forceinline__ void load_keys(const SpanParams& p, int blk, int g, int key, int quarter, Frag<D>& f) {
   blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
   const uint4* row = static_cast<const uint4*>(p.k_cache) +
                      (((size_t)blk * p.Hkv + g) * kBlock + (key & 15)) * (D / 8);
 #pragma unroll
   for (int s = 0; s < Frag<D>::KSTEPS; ++s) f.k[s] = row[4 * s + quarter];
+}
+
+// A stream of key groups (kSmGroup tiles of 16 keys; group n starts at key first + n * step) run
+// as a three-stage pipeline per wave: block ids two groups ahead, K rows one group ahead,
+// arithmetic on the current group - so neither load latency sits on the critical path.
+// `use(tile_first_key, scores)` is called for every tile whose first key is below `end`.
+template <int D, typename F>
+__device__ __forceinline__ void stream_keys(const SpanParams& p, const int* bt, int g, int j, int quarter,
+                                            const bf16x8 (&qf)[D / 32], int first, int step, int end, int pos_max,
+                                            F&& use) {
+  auto lane_key = [&](int base, int u) { return min(base + 16 * u + j, pos_max); };
+  auto ids = [&](int base, int (&id)[kSmGroup]) {
+#pragma unroll
+    for (int u = 0; u < kSmGroup; ++u) id[u] = bt[lane_key(base, u) >> 4];
+  };
+  auto rows = [&](int base, const int (&id)[kSmGroup], Frag<D> (&f)[kSmGroup]) {
+#pragma unroll
+    for (int u = 0; u < kSmGroup; ++u) load_keys<D>(p, id[u], g, lane_key(base, u), quarter, f[u]);
+  };
+  auto work = [&](int base, const Frag<D> (&f)[kSmGroup]) {
+#pragma unroll
+    for (int u = 0; u < kSmGroup; ++u)
+      if (base + 16 * u < end) use(base + 16 * u, scores<D>(f[u], qf));   // uniform
+  };
+  if (first >= end) return;
+  // Every load below is issued unconditionally - keys are clamped into the sequence, so reading a
+  // group past `end` is harmless - because the compiler can only keep loads in flight across a
+  // wait when their number does not depend on the path taken.
+  int idA[kSmGroup], idB[kSmGroup];
+  Frag<D> fA[kSmGroup], fB[kSmGroup];
+  ids(first, idA);
+  rows(first, idA, fA);
+  ids(first + step, idB);
+  for (int base = first; base < end; base += 2 * step) {
+    // fA holds (or awaits) the rows of `base`, idB the ids of base + step.  Loads return in issue
+    // order, so ids are requested BEFORE the rows of the group in front of them: waiting for ids
+    // then never drains rows issued after them.
+    int idC[kSmGroup];
+    ids(base + 2 * step, idC);
+    rows(base + step, idB, fB);
+    work(base, fA);
+    ids(base + 3 * step, idB);
+    rows(base + 2 * step, idC, fA);
+    work(base + step, fB);
+  }
 }
 
 template <int D>
@@ -78,7 +125,8 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
   __shared__ float sh_l[kSmWaves][kSmRows];
 
   const int i = blockIdx.z, ps = blockIdx.y, rb = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps the key loops scalar
   const int j = lane & 15, quarter = lane >> 4;
 
   const int Lraw = p.seq_lens[i];
@@ -113,35 +161,25 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
   // ---- pass 1: row maximum and normaliser
   float m = -INFINITY, l = 0.0f;
   const int ntile = pos_max / 16 + 1;
-  for (int b0 = wave * kSmGroup; b0 < ntile; b0 += kSmWaves * kSmGroup) {
-    Frag<D> f[kSmGroup];
+  stream_keys<D>(p, bt, g, j, quarter, qf, 16 * kSmGroup * wave, 16 * kSmGroup * kSmWaves, 16 * ntile, pos_max,
+                 [&](int key0, const f32x4 s4) {
+    float sv[4];
+    float mt = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < kSmGroup; ++u) {
-      const int key = min(16 * (b0 + u) + j, pos_max);
-      load_keys<D>(p, bt, g, key, quarter, f[u]);
+    for (int r = 0; r < 4; ++r) {
+      const int key = key0 + 4 * quarter + r;
+      sv[r] = key <= pos ? s4[r] * c : -INFINITY;
+      mt = fmaxf(mt, sv[r]);
     }
+    // branch-free update (a divergent branch between the loads would make the compiler wait for
+    // every load in flight): with everything masked so far the reference is 0 and all terms vanish
+    const float mn = fmaxf(m, mt);
+    const float ref = (mn == -INFINITY) ? 0.0f : mn;
+    l *= fast_exp2(m - ref);                        // m = -inf: l is 0 and stays 0
 #pragma unroll
-    for (int u = 0; u < kSmGroup; ++u) {
-      if (b0 + u >= ntile) continue;               // uniform
-      const f32x4 s4 = scores<D>(f[u], qf);
-      float sv[4];
-      float mt = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int key = 16 * (b0 + u) + 4 * quarter + r;
-        sv[r] = key <= pos ? s4[r] * c : -INFINITY;
-        mt = fmaxf(mt, sv[r]);
-      }
-      if (mt > m) {
-        l *= fast_exp2(m - mt);                     // m = -inf gives 0 * l with l = 0
-        m = mt;
-      }
-      if (m != -INFINITY) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) l += fast_exp2(sv[r] - m);
-      }
-    }
-  }
+    for (int r = 0; r < 4; ++r) l += fast_exp2(sv[r] - ref);
+    m = mn;
+  });
   // merge the four quarters of a row, then the waves
 #pragma unroll
   for (int off = 16; off <= 32; off <<= 1) {
@@ -170,28 +208,186 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
     const int e = min(p.key_spans[((size_t)i * p.S + r) * 2 + 1], pos_max + 1);
     if (e <= a) continue;                          // uniform; mass was zero-filled
     float acc = 0.0f;
-    for (int k0 = a; k0 < e; k0 += 16 * kSmGroup) {
-      Frag<D> f[kSmGroup];
+    stream_keys<D>(p, bt, g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max, [&](int key0, const f32x4 s4) {
 #pragma unroll
-      for (int u = 0; u < kSmGroup; ++u) {
-        const int key = min(k0 + 16 * u + j, pos_max);
-        load_keys<D>(p, bt, g, key, quarter, f[u]);
+      for (int rr = 0; rr < 4; ++rr) {
+        const int key = key0 + 4 * quarter + rr;
+        acc += (key < e && key <= pos) ? fast_exp2(s4[rr] * c - M) : 0.0f;
       }
-#pragma unroll
-      for (int u = 0; u < kSmGroup; ++u) {
-        if (k0 + 16 * u >= e) continue;            // uniform
-        const f32x4 s4 = scores<D>(f[u], qf);
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const int key = k0 + 16 * u + 4 * quarter + rr;
-          if (key < e && key <= pos) acc += fast_exp2(s4[rr] * c - M);
-        }
-      }
-    }
+    });
     acc += __shfl_xor(acc, 16);
     acc += __shfl_xor(acc, 32);
     if (quarter == 0 && row_ok) mrow[r] = acc * inv;
   }
+}
+
+// ---- the same two passes as two kernels, for callers that provide scratch memory: a single
+// workgroup per row block has to pull a long sequence's keys through one CU (about 100 us per
+// 10 k keys and pass); here pass 1 is split over the keys and pass 2 over the spans, so the
+// work spreads over the chip.
+
+// What both kernels need to know about their row block; false if there is nothing to do.
+struct RowBlock {
+  int g, h, row0, pos, pos_max, slot0;
+  bool row_ok;
+};
+
+__device__ __forceinline__ bool row_block(const SpanParams& p, int i, int ps, int rb, int j, RowBlock& r) {
+  const int Lraw = p.seq_lens[i];
+  r.row0 = p.cu_q_lens[i];
+  const int n = p.cu_q_lens[i + 1] - r.row0;
+  const int L = min(Lraw, p.max_blocks * kBlock);
+  if (Lraw < 0 || n <= 0 || n > L || r.row0 < 0 || r.row0 + n > p.total_q) return false;
+  r.h = p.probe_heads[ps];
+  if ((unsigned)r.h >= (unsigned)p.Hq) return false;
+  r.g = r.h / p.G;
+  const int qb = p.query_sel[2 * i];
+  const int qe = min(min(p.query_sel[2 * i + 1], n), qb + p.NQ);
+  r.slot0 = kSmRows * rb;
+  const int t_lo = max(qb + r.slot0, 0), t_hi = min(qb + r.slot0 + kSmRows, qe);
+  if (t_hi <= t_lo) return false;
+  const int t_mine = qb + r.slot0 + j;
+  r.row_ok = t_mine >= t_lo && t_mine < t_hi;
+  const int t = min(max(t_mine, t_lo), t_hi - 1);
+  r.pos = L - n + t;
+  r.pos_max = L - n + t_hi - 1;
+  r.row0 += t;      // global q row of this lane
+  return true;
+}
+
+template <int D>
+__device__ __forceinline__ void load_q(const SpanParams& p, const RowBlock& r, int quarter, bf16x8 (&qf)[D / 32]) {
+  const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.q) + ((size_t)r.row0 * p.Hq + r.h) * D);
+#pragma unroll
+  for (int s = 0; s < D / 32; ++s) qf[s] = qp[4 * s + quarter];
+}
+
+constexpr int kSplitWaves = 4;
+
+template <int D>
+__global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParams p) {
+  __shared__ float sh_m[kSplitWaves][kSmRows];
+  __shared__ float sh_l[kSplitWaves][kSmRows];
+  // every workgroup helps zero-filling mass (the second kernel writes only entries with a row and a span)
+  {
+    const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
+    const size_t nthreads = (size_t)gridDim.x * gridDim.y * gridDim.z * blockDim.x;
+    const size_t me = (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    for (size_t x = me; x < nmass; x += nthreads) p.mass[x] = 0.0f;
+  }
+  const int i = blockIdx.z / p.nsplit, sp = blockIdx.z % p.nsplit, ps = blockIdx.y, rb = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane & 15, quarter = lane >> 4;
+  RowBlock r;
+  if (!row_block(p, i, ps, rb, j, r)) return;   // uniform
+  const int* bt = p.block_table + (size_t)i * p.max_blocks;
+  bf16x8 qf[D / 32];
+  load_q<D>(p, r, quarter, qf);
+  const float c = p.scale_log2;
+  const int ntile = r.pos_max / 16 + 1;
+  const int per = (ntile + p.nsplit - 1) / p.nsplit;           // tiles per split
+  const int lo = 16 * per * sp, hi = min(16 * per * (sp + 1), 16 * ntile);
+  const int pos = r.pos;
+  float m = -INFINITY, l = 0.0f;
+  stream_keys<D>(p, bt, r.g, j, quarter, qf, lo + 16 * kSmGroup * wave, 16 * kSmGroup * kSplitWaves, hi, r.pos_max,
+                 [&](int key0, const f32x4 s4) {
+    float sv[4];
+    float mt = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int key = key0 + 4 * quarter + q;
+      sv[q] = key <= pos ? s4[q] * c : -INFINITY;
+      mt = fmaxf(mt, sv[q]);
+    }
+    const float mn = fmaxf(m, mt);
+    const float ref = (mn == -INFINITY) ? 0.0f : mn;
+    l *= fast_exp2(m - ref);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) l += fast_exp2(sv[q] - ref);
+    m = mn;
+  });
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {
+    const float mo = __shfl_xor(m, off), lo2 = __shfl_xor(l, off);
+    const float mn = fmaxf(m, mo);
+    if (mn != -INFINITY) l = l * fast_exp2(m - mn) + lo2 * fast_exp2(mo - mn);
+    m = mn;
+  }
+  if (quarter == 0) { sh_m[wave][j] = m; sh_l[wave][j] = l; }
+  __syncthreads();
+  if (threadIdx.x < kSmRows) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kSplitWaves; ++w) M = fmaxf(M, sh_m[w][j]);
+    float Ls = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kSplitWaves; ++w) {
+      const float mw = sh_m[w][j];
+      if (mw != -INFINITY) Ls += sh_l[w][j] * fast_exp2(mw - M);
+    }
+    p.stats[(((size_t)i * p.P + ps) * p.nq_pad + r.slot0 + j) * p.nsplit + sp] = make_float2(M, Ls);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kSplitWaves * 64) void k_span_sums(const SpanParams p) {
+  const int i = blockIdx.z / p.sgroups, sg = blockIdx.z % p.sgroups, ps = blockIdx.y, rb = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane & 15, quarter = lane >> 4;
+  RowBlock r;
+  if (!row_block(p, i, ps, rb, j, r)) return;   // uniform
+  const int* bt = p.block_table + (size_t)i * p.max_blocks;
+  bf16x8 qf[D / 32];
+  load_q<D>(p, r, quarter, qf);
+  const float c = p.scale_log2;
+  // the row's softmax maximum and normaliser from the key splits of the first kernel
+  const float2* st = p.stats + (((size_t)i * p.P + ps) * p.nq_pad + r.slot0 + j) * p.nsplit;
+  float M = -INFINITY;
+  for (int sp = 0; sp < p.nsplit; ++sp) M = fmaxf(M, st[sp].x);
+  float Lsum = 0.0f;
+  for (int sp = 0; sp < p.nsplit; ++sp) {
+    const float2 v = st[sp];
+    if (v.x != -INFINITY) Lsum += v.y * fast_exp2(v.x - M);
+  }
+  const float inv = 1.0f / Lsum;
+  const int pos = r.pos;
+  float* mrow = p.mass + (((size_t)i * p.P + ps) * p.NQ + (r.slot0 + j)) * p.S;
+  for (int s = sg * kSplitWaves + wave; s < p.S; s += p.sgroups * kSplitWaves) {
+    const int a = max(p.key_spans[((size_t)i * p.S + s) * 2], 0);
+    const int e = min(p.key_spans[((size_t)i * p.S + s) * 2 + 1], r.pos_max + 1);
+    if (e <= a) continue;                          // uniform; mass was zero-filled
+    float acc = 0.0f;
+    stream_keys<D>(p, bt, r.g, j, quarter, qf, a, 16 * kSmGroup, e, r.pos_max, [&](int key0, const f32x4 s4) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int key = key0 + 4 * quarter + q;
+        acc += (key < e && key <= pos) ? fast_exp2(s4[q] * c - M) : 0.0f;
+      }
+    });
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (quarter == 0 && r.row_ok) mrow[s] = acc * inv;
+  }
+}
+
+// geometry of the split path from host scalars only
+struct SplitGeom { int nsplit, sgroups, nq_pad; size_t bytes; bool usable; };
+
+inline SplitGeom split_geometry(const hook_attn_probe_args* a) {
+  SplitGeom g{};
+  const long long max_ctx = (long long)a->max_blocks_per_seq * kBlock;
+  g.nsplit = (int)((max_ctx + 2047) / 2048);
+  if (g.nsplit < 1) g.nsplit = 1;
+  if (g.nsplit > 16) g.nsplit = 16;
+  g.sgroups = (a->max_spans + 2 * kSplitWaves - 1) / (2 * kSplitWaves);
+  if (g.sgroups < 1) g.sgroups = 1;
+  if (g.sgroups > 32) g.sgroups = 32;
+  g.nq_pad = (a->max_sel_q + kSmRows - 1) / kSmRows * kSmRows;
+  g.bytes = (size_t)a->num_seqs * a->num_probe_heads * g.nq_pad * g.nsplit * sizeof(float2);
+  g.usable = (long long)a->num_seqs * g.nsplit <= 65535 && (long long)a->num_seqs * g.sgroups <= 65535;
+  return g;
 }
 
 __global__ __launch_bounds__(256) void k_zero_mass(float* ptr, size_t n) {
@@ -229,6 +425,24 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   p.query_sel = a->query_sel; p.S = a->max_spans; p.key_spans = a->key_spans; p.mass = a->mass;
   hipStream_t st = static_cast<hipStream_t>(a->stream);
 
+  // with enough scratch memory: pass 1 split over the keys, pass 2 over the spans
+  const SplitGeom geo = split_geometry(a);
+  if (geo.usable && a->workspace && a->workspace_bytes >= geo.bytes &&
+      (reinterpret_cast<uintptr_t>(a->workspace) % 8) == 0) {
+    p.stats = static_cast<float2*>(a->workspace);
+    p.nsplit = geo.nsplit; p.sgroups = geo.sgroups; p.nq_pad = geo.nq_pad;
+    const unsigned gx = (unsigned)(geo.nq_pad / kSmRows);
+    const dim3 ga(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.nsplit)), gb(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.sgroups));
+    if (a->head_dim == 128) {
+      hipLaunchKernelGGL(k_span_stats<128>, ga, dim3(kSplitWaves * 64), 0, st, p);
+      hipLaunchKernelGGL(k_span_sums<128>, gb, dim3(kSplitWaves * 64), 0, st, p);
+    } else {
+      hipLaunchKernelGGL(k_span_stats<64>, ga, dim3(kSplitWaves * 64), 0, st, p);
+      hipLaunchKernelGGL(k_span_sums<64>, gb, dim3(kSplitWaves * 64), 0, st, p);
+    }
+    return hipGetLastError() == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
+  }
+
   const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
   size_t zb = (nmass + 2047) / 2048;
   if (zb > 2048) zb = 2048;
@@ -238,4 +452,12 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   if (a->head_dim == 128) hipLaunchKernelGGL(k_span_mass<128>, grid, dim3(kSmWaves * 64), 0, st, p);
   else hipLaunchKernelGGL(k_span_mass<64>, grid, dim3(kSmWaves * 64), 0, st, p);
   return hipGetLastError() == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
+}
+
+extern "C" size_t hook_span_mass_workspace_bytes(const hook_attn_probe_args* a) {
+  if (!a || a->num_seqs <= 0 || a->num_probe_heads <= 0 || a->max_sel_q <= 0 || a->max_spans <= 0 ||
+      a->max_blocks_per_seq <= 0)
+    return 0;
+  const hook::SplitGeom g = hook::split_geometry(a);
+  return g.usable ? g.bytes : 0;
 }

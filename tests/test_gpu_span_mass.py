@@ -24,15 +24,17 @@ def _check(b):
     from paper_2603_06588_amd import binding
     _, want = oracle.attn_probe_batch(b, rows=_selected_rows(b))
     bd = b.to(DEV)
-    got = binding.hook_span_mass_batch(bd)
-    torch.cuda.synchronize()
-    again = binding.hook_span_mass_batch(bd)
-    torch.cuda.synchronize()
-    assert torch.equal(got, again)                                   # reproducible bit for bit
-    got = got.cpu().double()
-    assert torch.isfinite(got).all()
-    err = (got - want).abs().max().item()
-    assert err <= MASS_TOL, err
+    # both forms: split over keys and spans (scratch memory given), and one workgroup per row block
+    for use_ws in (False, True):
+        got = binding.hook_span_mass_batch(bd, use_workspace=use_ws)
+        torch.cuda.synchronize()
+        again = binding.hook_span_mass_batch(bd, use_workspace=use_ws)
+        torch.cuda.synchronize()
+        assert torch.equal(got, again)                               # reproducible bit for bit
+        got = got.cpu().double()
+        assert torch.isfinite(got).all()
+        err = (got - want).abs().max().item()
+        assert err <= MASS_TOL, (use_ws, err)
     return got, want
 
 
@@ -103,7 +105,9 @@ def test_span_mass_with_invalid_device_contents_completes():
     bad.key_spans = bad.key_spans.clone()
     bad.key_spans[1, 0, 0], bad.key_spans[1, 0, 1] = -2**31, 2**31 - 1
     bad.key_spans[1, 1, 0], bad.key_spans[1, 1, 1] = 2**31 - 1, -2**31
-    got = binding.hook_span_mass_batch(bad).cpu().double()
+    for use_ws in (False, True):
+        got = binding.hook_span_mass_batch(bad, use_workspace=use_ws).cpu().double()
+        assert torch.isfinite(got).all()
     assert torch.isfinite(got).all()
     assert (got[0] - want[0]).abs().max() <= MASS_TOL
     assert (got[2] == 0).all()
