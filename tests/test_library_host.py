@@ -90,6 +90,13 @@ def test_span_mass_argument_checks(binding):
     assert lib.hook_span_mass(ctypes.byref(a)) == 3            # fp32 inputs are not supported here
     a.dtype, a.num_probe_heads = 0, 0
     assert lib.hook_span_mass(ctypes.byref(a)) == 2            # nothing to probe
+    # scratch size of the split form: none for a null struct, grows with rows and context length
+    assert lib.hook_span_mass_workspace_bytes(None) == 0
+    a.num_probe_heads, a.max_blocks_per_seq = 2, 64
+    small = lib.hook_span_mass_workspace_bytes(ctypes.byref(a))
+    a.max_blocks_per_seq, a.max_sel_q = 1024, 64
+    big = lib.hook_span_mass_workspace_bytes(ctypes.byref(a))
+    assert big > small > 0 and small % 8 == 0 and big % 8 == 0
 
 
 def test_reduce_struct_and_argument_checks(binding):
