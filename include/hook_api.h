@@ -72,7 +72,7 @@ typedef enum hook_batch_kind {
 
 #define HOOK_MAX_SPANS 8      /* S: key spans per sequence (hook_attn_probe) */
 #define HOOK_MAX_SPANS_WIDE 1024  /* S for hook_span_mass and hook_reduce_mass */
-#define HOOK_MAX_SEL_Q 4096   /* NQ: selected query rows per sequence */
+#define HOOK_MAX_SEL_Q 65536  /* NQ: selected query rows per sequence */
 #define HOOK_BLOCK_SIZE 16    /* tokens per KV-cache block */
 
 /*

@@ -3,7 +3,8 @@ import pytest
 import torch
 
 from paper_2603_06588_amd import workloads as W
-from helpers import bits, compare_with_oracle, run_hip
+import oracle
+from helpers import MASS_ATOL as MASS_TOL, bits, compare_with_oracle, run_hip
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +63,37 @@ def test_many_spans_and_rows():
                        max_spans=8)
     b.query_sel[0, 0], b.query_sel[0, 1] = 180, 250   # spans two row blocks and a tile edge
     _check(b, label="many_spans")
+
+
+def test_all_rows_selected_beyond_4096():
+    """Every row of a 4500-token prompt selected (the all-tokens query mode on a long prompt).  The
+    oracle checks output and masses on a sample of rows; a span over the whole context pins the
+    other rows (its mass is 1 at every row)."""
+    L = 4500
+    b = W.random_batch(125, [L, 300], [L, 300], 4, 2, 128, torch.bfloat16, num_probe_heads=2, max_sel_q=L,
+                       max_spans=2)
+    b.query_sel[0, 0], b.query_sel[0, 1] = 0, L
+    b.key_spans[0, 1, 0], b.key_spans[0, 1, 1] = 0, L
+    rows = sorted(set(list(range(0, 40)) + list(range(4080, 4120)) + list(range(L - 20, L + 300)) +
+                      torch.randint(0, L, (64,), generator=torch.Generator().manual_seed(5)).tolist()))
+    print(f"[case] all_rows_4500 sampled rows={len(rows)}", flush=True)
+    out, mass = run_hip(b.to(DEV))
+    assert mass.shape == (2, 2, L, 2)
+    ref_out, ref_mass = oracle.attn_probe_batch(b, rows=rows)
+    idx = torch.tensor(rows)
+    err = (out.cpu().double()[idx] - ref_out[idx]).abs().max().item()
+    assert err <= 2e-2 and err <= 2e-2 * ref_out[idx].abs().max().item()
+    got = mass.cpu().double()
+    long_rows = torch.tensor([t for t in rows if t < L])
+    assert (got[0][:, long_rows] - ref_mass[0][:, long_rows]).abs().max().item() <= MASS_TOL
+    assert (got[1] - ref_mass[1]).abs().max().item() <= MASS_TOL          # all 300 rows of the short one
+    assert (got[0, :, :, 1] - 1.0).abs().max().item() <= MASS_TOL
+    assert got.min().item() >= 0.0 and got.max().item() <= 1.0 + MASS_TOL
+    # the separate span pass accepts the same selection and agrees with the attention kernels
+    from paper_2603_06588_amd import binding
+    wide = binding.hook_span_mass_batch(b.to(DEV))
+    torch.cuda.synchronize()
+    assert (wide.cpu().double() - got).abs().max().item() <= MASS_TOL
 
 
 def test_fp32_small():
