@@ -172,3 +172,19 @@ def test_workspace_size_grows_with_decode_capacity(binding):
     small = lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, num_seqs=4, total_q=4, max_blocks_per_seq=64)))
     big = lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, num_seqs=4, total_q=4, max_blocks_per_seq=512)))
     assert big > small > 0
+
+
+def test_plain_c_program_compiles_links_and_runs(binding, tmp_path):
+    """include/hook_api.h is a C header: a C99 program (tests/c_abi_client.c) built with gcc -pedantic
+    links every entry point and gets the documented answers from the host-side checks."""
+    import subprocess
+    binding.load_library()
+    libdir = os.path.dirname(binding.LIB_PATH)
+    exe = str(tmp_path / "c_abi_client")
+    cc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
+                         "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_client.c"),
+                         "-o", exe, "-L", libdir, "-lhook", f"-Wl,-rpath,{libdir}"],
+                        capture_output=True, text=True)
+    assert cc.returncode == 0, cc.stdout + cc.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0, run.stdout + run.stderr
