@@ -51,20 +51,21 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   if (blockIdx.x != 0) return;
 
   __shared__ int hist[kPlanBuckets];
-  __shared__ int scan[kPlanBuckets];
   __shared__ int sh_cnt[kChunkSizes];   // number of decode chunks for each candidate size
   __shared__ int sh_status;
   __shared__ int sh_dec_next;
   __shared__ int sh_dec_total;   // decode items actually written
   __shared__ int sh_nlist;
   __shared__ int sh_list[kListCap];
+  __shared__ int4 sh_list_info[kListCap];   // {L, n, row0, -} of the queued sequences: read once
   __shared__ int dhist[kDecBuckets + 1];   // decode items by length in cache blocks (<= 2048 / 16)
+  __shared__ int sh_wsum[kPlanThreads / 64];
 
   for (int b = tid; b < kPlanBuckets; b += kPlanThreads) hist[b] = 0;
   if (tid < kChunkSizes) sh_cnt[tid] = 0;
   if (tid == 0) sh_status = 0;
   if (tid <= kDecBuckets) dhist[tid] = 0;
-  if (tid == 0) { sh_dec_next = 0; sh_nlist = 0; }
+  if (tid == 0) { sh_dec_next = 0; sh_nlist = 0; sh_dec_total = 0; }
   __syncthreads();
 
   // pass 1: histogram of prefill items by tile count, decode chunk counts per candidate size
@@ -87,6 +88,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       const int pos = atomicAdd(&sh_nlist, 1);
       if (pos < kListCap) {
         sh_list[pos] = i;
+        sh_list_info[pos] = make_int4(s.L, s.n, s.row0, 0);
       } else {
         for (int r0 = 0; r0 < s.n; r0 += p.rows_per_wg) {
           const int last = min(r0 + p.rows_per_wg, s.n) - 1;
@@ -111,8 +113,9 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   __syncthreads();
   const int nlist = min(sh_nlist, kListCap);
   for (int k = wave; k < nlist; k += kWaves) {
-    int dummy = 0;
-    const SeqInfo s = read_seq(p, sh_list[k], &dummy);
+    const int4 info = sh_list_info[k];
+    SeqInfo s;
+    s.L = info.x; s.n = info.y; s.row0 = info.z; s.kind = 1;
     for (int r0 = lane * p.rows_per_wg; r0 < s.n; r0 += 64 * p.rows_per_wg) {
       const int last = min(r0 + p.rows_per_wg, s.n) - 1;
       const int tiles = (s.L - s.n + last) / kTileKeys + 1;
@@ -121,29 +124,32 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   }
   __syncthreads();
 
-  // descending exclusive offsets: scan[b] = number of items in buckets above b.  Only buckets
-  // up to the longest possible sequence can be populated; they sit at the END of the reversed
-  // array, so the Hillis-Steele steps needed are those that reach across that populated tail.
-  for (int b = tid; b < kPlanBuckets; b += kPlanThreads) scan[b] = hist[kPlanBuckets - 1 - b];
-  __syncthreads();
-  const int max_bucket = min(kPlanBuckets - 1, (p.max_blocks * kBlock - 1) / kTileKeys + 1);
-  for (int off = 1; off <= max_bucket; off <<= 1) {
-    int v[kPlanBuckets / kPlanThreads];
+  // descending exclusive offsets: bucket b starts after all items of the buckets above it.  Every
+  // thread owns two neighbouring buckets; a wave scan plus the wave totals give the offsets with
+  // two barriers.  A batch without query chunks skips it.
+  static_assert(kPlanBuckets == 2 * kPlanThreads, "two buckets per planner thread");
+  int n_prefill = 0;
+  if (sh_nlist > 0) {   // uniform
+    const int hi = kPlanBuckets - 1 - 2 * tid, lo = hi - 1;   // this thread's buckets, longest first
+    const int c_hi = hist[hi], c_lo = hist[lo];
+    int inc = c_hi + c_lo;
 #pragma unroll
-    for (int k = 0; k < kPlanBuckets / kPlanThreads; ++k) {
-      const int b = tid + k * kPlanThreads;
-      v[k] = scan[b] + (b >= off ? scan[b - off] : 0);
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(inc, off);
+      if (lane >= off) inc += t;
     }
+    if (lane == 63) sh_wsum[wave] = inc;
     __syncthreads();
+    int before = 0;
 #pragma unroll
-    for (int k = 0; k < kPlanBuckets / kPlanThreads; ++k) scan[tid + k * kPlanThreads] = v[k];
-    __syncthreads();
-  }
-  // scan is now inclusive over reversed buckets; turn bucket b's slot into its running cursor
-  const int n_prefill = scan[kPlanBuckets - 1];
-  for (int b = tid; b < kPlanBuckets; b += kPlanThreads) {
-    const int rb = kPlanBuckets - 1 - b;  // position of bucket b in the reversed order
-    hist[b] = scan[rb] - hist[b];         // exclusive start (hist[b] still holds the count)
+    for (int w = 0; w < kWaves; ++w) {
+      const int v = sh_wsum[w];
+      before += (w < wave) ? v : 0;
+      n_prefill += v;
+    }
+    const int start = before + inc - (c_hi + c_lo);
+    hist[hi] = start;            // running cursors of the scatter pass
+    hist[lo] = start + c_hi;
   }
   // chunk size: every workgroup pays a few microseconds of start-up and merge, so long chunks
   // stream best; take the largest candidate that still yields at least 2048 decode workgroups
@@ -158,22 +164,40 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   // pass 2: scatter.  What the ordering pass below needs about a thread's first sequence stays
   // in registers (batches of up to kPlanThreads sequences never re-read anything).
   int2 my_sd = make_int2(0, 0);
-  for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
-    int dummy = 0;
-    const SeqInfo s = (i == tid) ? my_s : read_seq(p, i, &dummy);
-    int2 sd = make_int2(0, 0);
-    if (s.kind == 2) {
-      const int nch = (s.L + chunk - 1) / chunk;
-      const int base = atomicAdd(&sh_dec_next, nch);
-      if (base + nch <= p.dec_cap) {
-        sd = make_int2(base, nch);
-        for (int c = 0; c < nch; ++c) p.dec_items[base + c] = make_int4(i, c, s.L, s.row0);
-        // every chunk but the last is full
-        if (nch > 1) atomicAdd(&dhist[chunk / kBlock], nch - 1);
-        atomicAdd(&dhist[(s.L - (nch - 1) * chunk + kBlock - 1) / kBlock], 1);
-      }
+  // the trip count is uniform so that the lanes of a wave can pool their requests: one atomic per
+  // wave for the item range and one for the bucket of full chunks (lanes hitting one LDS address
+  // are served one at a time)
+  for (int i0 = 0; i0 < p.num_seqs; i0 += kPlanThreads) {
+    const int i = i0 + tid;
+    SeqInfo s;
+    s.L = s.n = s.row0 = s.kind = 0;
+    if (i < p.num_seqs) {
+      int dummy = 0;
+      s = (i == tid) ? my_s : read_seq(p, i, &dummy);
     }
-    p.seq_dec[i] = sd;
+    const int nch = (s.kind == 2) ? (s.L + chunk - 1) / chunk : 0;
+    int inc = nch;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(inc, off);
+      if (lane >= off) inc += t;
+    }
+    int wbase = 0;
+    if (lane == 63 && inc > 0) wbase = atomicAdd(&sh_dec_next, inc);
+    wbase = __shfl(wbase, 63);
+    const int base = wbase + inc - nch;
+    int2 sd = make_int2(0, 0);
+    if (nch > 0 && base + nch <= p.dec_cap) {
+      sd = make_int2(base, nch);
+      for (int c = 0; c < nch; ++c) p.dec_items[base + c] = make_int4(i, c, s.L, s.row0);
+      atomicAdd(&dhist[(s.L - (nch - 1) * chunk + kBlock - 1) / kBlock], 1);
+    }
+    // every chunk but the last is full
+    int full = sd.y > 1 ? sd.y - 1 : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) full += __shfl_xor(full, off);
+    if (lane == 0 && full > 0) atomicAdd(&dhist[chunk / kBlock], full);
+    if (i < p.num_seqs) p.seq_dec[i] = sd;
     if (i == tid) my_sd = sd;
   }
   auto scatter_rows = [&](int i, const SeqInfo& s, int first, int step) {
@@ -188,10 +212,10 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     }
   };
   for (int k = wave; k < nlist; k += kWaves) {
-    int dummy = 0;
-    const int i = sh_list[k];
-    const SeqInfo s = read_seq(p, i, &dummy);
-    scatter_rows(i, s, lane, 64);
+    const int4 info = sh_list_info[k];
+    SeqInfo s;
+    s.L = info.x; s.n = info.y; s.row0 = info.z; s.kind = 1;
+    scatter_rows(sh_list[k], s, lane, 64);
   }
   if (sh_nlist > kListCap) {   // sequences that did not fit the queue
     for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
@@ -206,7 +230,8 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   __syncthreads();
   // processing order of the decode items: by decreasing length, so that the short last chunks
   // of the sequences fill the end of the launch instead of being scattered through it
-  if (tid < 64) {   // exclusive offsets in descending bucket order: lanes take runs of buckets, then a wave scan
+  const bool any_decode = sh_dec_next > 0;   // uniform
+  if (any_decode && tid < 64) {   // exclusive offsets in descending bucket order: lanes take runs of buckets, then a wave scan
     constexpr int kPer = (kDecBuckets + 1 + 63) / 64;
     int loc[kPer];
     int sum = 0;
@@ -231,18 +256,38 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     if (tid == 63) sh_dec_total = inc;
   }
   __syncthreads();
-  for (int i = tid; i < p.num_seqs; i += kPlanThreads) {
-    int2 sd = my_sd;
-    int L = my_s.L;
-    if (i != tid) {
-      sd = p.seq_dec[i];   // written by this same thread above
-      if (sd.y == 0) continue;
-      int dummy = 0;
-      L = read_seq(p, i, &dummy).L;
-    }
-    for (int c = 0; c < sd.y; ++c) {
-      const int len = (c + 1 < sd.y) ? chunk : L - c * chunk;
-      p.dec_order[atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1)] = sd.x + c;
+  if (any_decode) {
+    for (int i0 = 0; i0 < p.num_seqs; i0 += kPlanThreads) {
+      const int i = i0 + tid;
+      int2 sd = make_int2(0, 0);
+      int L = 0;
+      if (i == tid) {
+        sd = my_sd;
+        L = my_s.L;
+      } else if (i < p.num_seqs) {
+        sd = p.seq_dec[i];   // written by this same thread above
+        if (sd.y > 0) {
+          int dummy = 0;
+          L = read_seq(p, i, &dummy).L;
+        }
+      }
+      // the full chunks of all lanes share one bucket: one cursor update per wave
+      const int full = sd.y > 1 ? sd.y - 1 : 0;
+      int inc = full;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+      }
+      int wbase = 0;
+      if (lane == 63 && inc > 0) wbase = atomicAdd(&dhist[chunk / kBlock], inc);
+      wbase = __shfl(wbase, 63);
+      const int pos = wbase + inc - full;
+      for (int c = 0; c < full; ++c) p.dec_order[pos + c] = sd.x + c;
+      if (sd.y > 0) {
+        const int len = L - (sd.y - 1) * chunk;
+        p.dec_order[atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1)] = sd.x + sd.y - 1;
+      }
     }
   }
   __syncthreads();
