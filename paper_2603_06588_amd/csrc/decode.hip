@@ -310,21 +310,65 @@ __global__ __launch_bounds__(256) void k_combine(const AttnParams p) {
   const float* rec0 = p.partials + ((size_t)sd.x * p.Hq + head) * C::PSTR;
   const size_t rstride = (size_t)p.Hq * C::PSTR;
 
+  // The records were written by other workgroups, possibly under another L2, so every first touch
+  // pays a trip to memory: the chunks' (max, sum) pairs are fetched one per lane in one go, and the
+  // accumulation below keeps four records in flight instead of walking them one by one.
   float mstar = -INFINITY;
-  for (int cidx = 0; cidx < sd.y; ++cidx) mstar = fmaxf(mstar, rec0[cidx * rstride + D]);
+  for (int c0 = 0; c0 < sd.y && sd.y > 1; c0 += 64) {
+    const float mc = (c0 + lane < sd.y) ? rec0[(size_t)(c0 + lane) * rstride + D] : -INFINITY;
+    mstar = fmaxf(mstar, mc);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, off));
   float l = 0.0f;
   float o[D / 64];
 #pragma unroll
   for (int e = 0; e < D / 64; ++e) o[e] = 0.0f;
   float a = 0.0f;  // lane s < S merges span s
-  for (int cidx = 0; cidx < sd.y; ++cidx) {
-    const float* rec = rec0 + cidx * rstride;
-    const float mc = rec[D];
-    const float wgt = (mc == -INFINITY) ? 0.0f : fast_exp2(mc - mstar);
-    l += wgt * rec[D + 1];
+  if (sd.y == 1) {   // a single chunk needs no weights: its record is the result up to the division
+    l = rec0[D + 1];
 #pragma unroll
-    for (int e = 0; e < D / 64; ++e) o[e] += wgt * rec[lane + 64 * e];
-    if (lane < kMaxSpans) a += wgt * rec[D + 2 + lane];
+    for (int e = 0; e < D / 64; ++e) o[e] = rec0[lane + 64 * e];
+    if (lane < kMaxSpans) a = rec0[D + 2 + lane];
+  }
+  for (int c0 = 0; c0 < sd.y && sd.y > 1; c0 += 64) {
+    // lane c holds the weight of chunk c0 + c
+    float wl = 0.0f, wgt_mine = 0.0f;
+    if (c0 + lane < sd.y) {
+      const float* rec = rec0 + (size_t)(c0 + lane) * rstride;
+      const float mc = rec[D];
+      wgt_mine = (mc == -INFINITY) ? 0.0f : fast_exp2(mc - mstar);
+      wl = wgt_mine * rec[D + 1];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off);
+    l += wl;
+    const int nc = min(64, sd.y - c0);
+    int c = 0;
+    for (; c + 4 <= nc; c += 4) {
+      float v[4][D / 64], sp[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float* rec = rec0 + (size_t)(c0 + c + u) * rstride;
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) v[u][e] = rec[lane + 64 * e];
+        sp[u] = (lane < kMaxSpans) ? rec[D + 2 + lane] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float wg = __shfl(wgt_mine, c + u);
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) o[e] += wg * v[u][e];
+        a += wg * sp[u];
+      }
+    }
+    for (; c < nc; ++c) {
+      const float* rec = rec0 + (size_t)(c0 + c) * rstride;
+      const float wg = __shfl(wgt_mine, c);
+#pragma unroll
+      for (int e = 0; e < D / 64; ++e) o[e] += wg * rec[lane + 64 * e];
+      if (lane < kMaxSpans) a += wg * rec[D + 2 + lane];
+    }
   }
   const float inv = 1.0f / l;
   const int qrow = p.cu_q_lens[seq];
