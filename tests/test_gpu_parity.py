@@ -307,6 +307,21 @@ def test_many_prefill_sequences_overflow_the_planner_queue():
     _check(b, label="planner_overflow")
 
 
+def test_many_decode_sequences_take_several_planner_trips():
+    # more single-row sequences than the planner has threads, ragged contexts from one key to several
+    # chunks, two query chunks and an empty sequence in between
+    lens, qlens = [], []
+    for i in range(2300):
+        L = 1 + (i * 37) % 700
+        lens.append(L)
+        qlens.append(1)
+    lens[5], qlens[5] = 90, 90
+    lens[1500], qlens[1500] = 300, 40
+    lens[2000], qlens[2000] = 0, 0
+    b = W.random_batch(181, lens, qlens, 4, 2, 128, torch.bfloat16, num_probe_heads=2, max_sel_q=1, max_spans=2)
+    _check(b, label="planner_many_decodes")
+
+
 def test_batch_kind_hint():
     """A correct hint changes nothing but the launches; a wrong one drops the contradicting
     sequences (rows untouched, mass zero) and sets bit 3 of the status word."""
