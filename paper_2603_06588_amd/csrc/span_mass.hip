@@ -2,7 +2,7 @@
 // a few heads: a probe-only pass that computes no attention output.  The attention call itself
 // then runs with probing switched off.
 //
-// Workgroup = (sequence, probed head, block of 16 selected rows), 16 waves.
+// Workgroup of the single-kernel form = (sequence, probed head, block of 16 selected rows), 16 waves.
 //   pass 1  the waves share the keys [0, pos_max] (32-key groups round-robin), each lane keeps a
 //           running (max, sum) for its row over the keys it sees; merged across lanes and waves
 //           into the exact softmax maximum and normaliser of each row;
@@ -62,13 +62,17 @@ __device__ __forceinline__ void load_keys(const SpanParams& p, int blk, int g, i
   for (int s = 0; s < Frag<D>::KSTEPS; ++s) f.k[s] = row[4 * s + quarter];
 }
 
+template <int D>
+__device__ __forceinline__ f32x4 scores(const Frag<D>& f, const bf16x8 (&qf)[D / 32]);
+
 // A stream of key groups (kSmGroup tiles of 16 keys; group n starts at key first + n * step) run
 // as a three-stage pipeline per wave: block ids two groups ahead, K rows one group ahead,
 // arithmetic on the current group - so neither load latency sits on the critical path.
-// `use(tile_first_key, scores)` is called for every tile whose first key is below `end`.
-template <int D, typename F>
+// `use(tile_first_key, scores[NB])` is called for every tile whose first key is below `end`; NB blocks
+// of 16 query rows share every K fetch.
+template <int D, int NB, typename F>
 __device__ __forceinline__ void stream_keys(const SpanParams& p, const int* bt, int g, int j, int quarter,
-                                            const bf16x8 (&qf)[D / 32], int first, int step, int end, int pos_max,
+                                            const bf16x8 (&qf)[NB][D / 32], int first, int step, int end, int pos_max,
                                             F&& use) {
   auto lane_key = [&](int base, int u) { return min(base + 16 * u + j, pos_max); };
   auto ids = [&](int base, int (&id)[kSmGroup]) {
@@ -82,7 +86,12 @@ __device__ __forceinline__ void stream_keys(const SpanParams& p, const int* bt, 
   auto work = [&](int base, const Frag<D> (&f)[kSmGroup]) {
 #pragma unroll
     for (int u = 0; u < kSmGroup; ++u)
-      if (base + 16 * u < end) use(base + 16 * u, scores<D>(f[u], qf));   // uniform
+      if (base + 16 * u < end) {   // uniform
+        f32x4 sc[NB];              // one K fetch serves the NB blocks of 16 rows
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) sc[nb] = scores<D>(f[u], qf[nb]);
+        use(base + 16 * u, sc);
+      }
   };
   if (first >= end) return;
   // Every load below is issued unconditionally - keys are clamped into the sequence, so reading a
@@ -149,20 +158,21 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
   const int pos_max = L - n + t_hi - 1;
 
   const int* bt = p.block_table + (size_t)i * p.max_blocks;
-  bf16x8 qf[D / 32];
+  bf16x8 qf[1][D / 32];
   {
     const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.q) +
                                                         ((size_t)(row0 + t) * p.Hq + h) * D);
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) qf[s] = qp[4 * s + quarter];
+    for (int s = 0; s < D / 32; ++s) qf[0][s] = qp[4 * s + quarter];
   }
   const float c = p.scale_log2;
 
   // ---- pass 1: row maximum and normaliser
   float m = -INFINITY, l = 0.0f;
   const int ntile = pos_max / 16 + 1;
-  stream_keys<D>(p, bt, g, j, quarter, qf, 16 * kSmGroup * wave, 16 * kSmGroup * kSmWaves, 16 * ntile, pos_max,
-                 [&](int key0, const f32x4 s4) {
+  stream_keys<D, 1>(p, bt, g, j, quarter, qf, 16 * kSmGroup * wave, 16 * kSmGroup * kSmWaves, 16 * ntile, pos_max,
+                    [&](int key0, const f32x4 (&sc)[1]) {
+    const f32x4 s4 = sc[0];
     float sv[4];
     float mt = -INFINITY;
 #pragma unroll
@@ -208,7 +218,8 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
     const int e = min(p.key_spans[((size_t)i * p.S + r) * 2 + 1], pos_max + 1);
     if (e <= a) continue;                          // uniform; mass was zero-filled
     float acc = 0.0f;
-    stream_keys<D>(p, bt, g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max, [&](int key0, const f32x4 s4) {
+    stream_keys<D, 1>(p, bt, g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max, [&](int key0, const f32x4 (&sc)[1]) {
+      const f32x4 s4 = sc[0];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const int key = key0 + 4 * quarter + rr;
@@ -263,11 +274,36 @@ __device__ __forceinline__ void load_q(const SpanParams& p, const RowBlock& r, i
 }
 
 constexpr int kSplitWaves = 4;
+constexpr int kSplitBlocks = 2;   // blocks of 16 rows per workgroup: they share every K fetch
+
+// The kSplitBlocks row blocks of workgroup column `bx`.  A block without rows shadows a block that
+// has some (same loads and arithmetic, nothing written); false if no block has rows.
+__device__ __forceinline__ bool row_blocks(const SpanParams& p, int i, int ps, int bx, int j,
+                                           RowBlock (&r)[kSplitBlocks], bool (&has)[kSplitBlocks], int& pos_max) {
+  int good = -1;
+#pragma unroll
+  for (int nb = 0; nb < kSplitBlocks; ++nb) {
+    has[nb] = row_block(p, i, ps, kSplitBlocks * bx + nb, j, r[nb]);
+    if (has[nb] && good < 0) good = nb;
+  }
+  if (good < 0) return false;
+  pos_max = 0;
+#pragma unroll
+  for (int nb = 0; nb < kSplitBlocks; ++nb) {
+    if (!has[nb]) {
+      r[nb] = r[good];
+      r[nb].slot0 = kSmRows * (kSplitBlocks * bx + nb);
+      r[nb].row_ok = false;
+    }
+    pos_max = max(pos_max, r[nb].pos_max);
+  }
+  return true;
+}
 
 template <int D>
 __global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParams p) {
-  __shared__ float sh_m[kSplitWaves][kSmRows];
-  __shared__ float sh_l[kSplitWaves][kSmRows];
+  __shared__ float sh_m[kSplitWaves][kSplitBlocks][kSmRows];
+  __shared__ float sh_l[kSplitWaves][kSplitBlocks][kSmRows];
   // every workgroup helps zero-filling mass (the second kernel writes only entries with a row and a span)
   {
     const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
@@ -275,100 +311,132 @@ __global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParam
     const size_t me = (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
     for (size_t x = me; x < nmass; x += nthreads) p.mass[x] = 0.0f;
   }
-  const int i = blockIdx.z / p.nsplit, sp = blockIdx.z % p.nsplit, ps = blockIdx.y, rb = blockIdx.x;
+  const int i = blockIdx.z / p.nsplit, sp = blockIdx.z % p.nsplit, ps = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, quarter = lane >> 4;
-  RowBlock r;
-  if (!row_block(p, i, ps, rb, j, r)) return;   // uniform
+  RowBlock r[kSplitBlocks];
+  bool has[kSplitBlocks];
+  int pos_max;
+  if (!row_blocks(p, i, ps, blockIdx.x, j, r, has, pos_max)) return;   // uniform
   const int* bt = p.block_table + (size_t)i * p.max_blocks;
-  bf16x8 qf[D / 32];
-  load_q<D>(p, r, quarter, qf);
+  bf16x8 qf[kSplitBlocks][D / 32];
+#pragma unroll
+  for (int nb = 0; nb < kSplitBlocks; ++nb) load_q<D>(p, r[nb], quarter, qf[nb]);
   const float c = p.scale_log2;
-  const int ntile = r.pos_max / 16 + 1;
+  const int ntile = pos_max / 16 + 1;
   const int per = (ntile + p.nsplit - 1) / p.nsplit;           // tiles per split
   const int lo = 16 * per * sp, hi = min(16 * per * (sp + 1), 16 * ntile);
-  const int pos = r.pos;
-  float m = -INFINITY, l = 0.0f;
-  stream_keys<D>(p, bt, r.g, j, quarter, qf, lo + 16 * kSmGroup * wave, 16 * kSmGroup * kSplitWaves, hi, r.pos_max,
-                 [&](int key0, const f32x4 s4) {
-    float sv[4];
-    float mt = -INFINITY;
+  float m[kSplitBlocks], l[kSplitBlocks];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int key = key0 + 4 * quarter + q;
-      sv[q] = key <= pos ? s4[q] * c : -INFINITY;
-      mt = fmaxf(mt, sv[q]);
+  for (int nb = 0; nb < kSplitBlocks; ++nb) { m[nb] = -INFINITY; l[nb] = 0.0f; }
+  stream_keys<D, kSplitBlocks>(p, bt, r[0].g, j, quarter, qf, lo + 16 * kSmGroup * wave, 16 * kSmGroup * kSplitWaves,
+                               hi, pos_max, [&](int key0, const f32x4 (&sc)[kSplitBlocks]) {
+#pragma unroll
+    for (int nb = 0; nb < kSplitBlocks; ++nb) {
+      float sv[4];
+      float mt = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int key = key0 + 4 * quarter + q;
+        sv[q] = key <= r[nb].pos ? sc[nb][q] * c : -INFINITY;
+        mt = fmaxf(mt, sv[q]);
+      }
+      const float mn = fmaxf(m[nb], mt);
+      const float ref = (mn == -INFINITY) ? 0.0f : mn;
+      l[nb] *= fast_exp2(m[nb] - ref);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) l[nb] += fast_exp2(sv[q] - ref);
+      m[nb] = mn;
     }
-    const float mn = fmaxf(m, mt);
-    const float ref = (mn == -INFINITY) ? 0.0f : mn;
-    l *= fast_exp2(m - ref);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) l += fast_exp2(sv[q] - ref);
-    m = mn;
   });
 #pragma unroll
-  for (int off = 16; off <= 32; off <<= 1) {
-    const float mo = __shfl_xor(m, off), lo2 = __shfl_xor(l, off);
-    const float mn = fmaxf(m, mo);
-    if (mn != -INFINITY) l = l * fast_exp2(m - mn) + lo2 * fast_exp2(mo - mn);
-    m = mn;
+  for (int nb = 0; nb < kSplitBlocks; ++nb) {
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float mo = __shfl_xor(m[nb], off), lo2 = __shfl_xor(l[nb], off);
+      const float mn = fmaxf(m[nb], mo);
+      if (mn != -INFINITY) l[nb] = l[nb] * fast_exp2(m[nb] - mn) + lo2 * fast_exp2(mo - mn);
+      m[nb] = mn;
+    }
+    if (quarter == 0) { sh_m[wave][nb][j] = m[nb]; sh_l[wave][nb][j] = l[nb]; }
   }
-  if (quarter == 0) { sh_m[wave][j] = m; sh_l[wave][j] = l; }
   __syncthreads();
-  if (threadIdx.x < kSmRows) {
+  if (threadIdx.x < kSplitBlocks * kSmRows) {
+    const int nb = threadIdx.x / kSmRows, jj = threadIdx.x % kSmRows;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kSplitWaves; ++w) M = fmaxf(M, sh_m[w][j]);
+    for (int w = 0; w < kSplitWaves; ++w) M = fmaxf(M, sh_m[w][nb][jj]);
     float Ls = 0.0f;
 #pragma unroll
     for (int w = 0; w < kSplitWaves; ++w) {
-      const float mw = sh_m[w][j];
-      if (mw != -INFINITY) Ls += sh_l[w][j] * fast_exp2(mw - M);
+      const float mw = sh_m[w][nb][jj];
+      if (mw != -INFINITY) Ls += sh_l[w][nb][jj] * fast_exp2(mw - M);
     }
-    p.stats[(((size_t)i * p.P + ps) * p.nq_pad + r.slot0 + j) * p.nsplit + sp] = make_float2(M, Ls);
+    const int slot = kSmRows * (kSplitBlocks * blockIdx.x + nb) + jj;
+    if (slot < p.nq_pad) p.stats[(((size_t)i * p.P + ps) * p.nq_pad + slot) * p.nsplit + sp] = make_float2(M, Ls);
   }
 }
 
 template <int D>
 __global__ __launch_bounds__(kSplitWaves * 64) void k_span_sums(const SpanParams p) {
-  const int i = blockIdx.z / p.sgroups, sg = blockIdx.z % p.sgroups, ps = blockIdx.y, rb = blockIdx.x;
+  const int i = blockIdx.z / p.sgroups, sg = blockIdx.z % p.sgroups, ps = blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, quarter = lane >> 4;
-  RowBlock r;
-  if (!row_block(p, i, ps, rb, j, r)) return;   // uniform
+  RowBlock r[kSplitBlocks];
+  bool has[kSplitBlocks];
+  int pos_max;
+  if (!row_blocks(p, i, ps, blockIdx.x, j, r, has, pos_max)) return;   // uniform
   const int* bt = p.block_table + (size_t)i * p.max_blocks;
-  bf16x8 qf[D / 32];
-  load_q<D>(p, r, quarter, qf);
+  bf16x8 qf[kSplitBlocks][D / 32];
+#pragma unroll
+  for (int nb = 0; nb < kSplitBlocks; ++nb) load_q<D>(p, r[nb], quarter, qf[nb]);
   const float c = p.scale_log2;
-  // the row's softmax maximum and normaliser from the key splits of the first kernel
-  const float2* st = p.stats + (((size_t)i * p.P + ps) * p.nq_pad + r.slot0 + j) * p.nsplit;
-  float M = -INFINITY;
-  for (int sp = 0; sp < p.nsplit; ++sp) M = fmaxf(M, st[sp].x);
-  float Lsum = 0.0f;
-  for (int sp = 0; sp < p.nsplit; ++sp) {
-    const float2 v = st[sp];
-    if (v.x != -INFINITY) Lsum += v.y * fast_exp2(v.x - M);
+  // each row's softmax maximum and normaliser from the key splits of the first kernel
+  float M[kSplitBlocks], inv[kSplitBlocks];
+#pragma unroll
+  for (int nb = 0; nb < kSplitBlocks; ++nb) {
+    M[nb] = 0.0f;
+    inv[nb] = 0.0f;
+    if (has[nb]) {   // uniform; a shadow block has no statistics of its own and writes nothing
+      const float2* st = p.stats + (((size_t)i * p.P + ps) * p.nq_pad + r[nb].slot0 + j) * p.nsplit;
+      float mx = -INFINITY;
+      for (int sp = 0; sp < p.nsplit; ++sp) mx = fmaxf(mx, st[sp].x);
+      float Lsum = 0.0f;
+      for (int sp = 0; sp < p.nsplit; ++sp) {
+        const float2 v = st[sp];
+        if (v.x != -INFINITY) Lsum += v.y * fast_exp2(v.x - mx);
+      }
+      M[nb] = mx;
+      inv[nb] = 1.0f / Lsum;
+    }
   }
-  const float inv = 1.0f / Lsum;
-  const int pos = r.pos;
-  float* mrow = p.mass + (((size_t)i * p.P + ps) * p.NQ + (r.slot0 + j)) * p.S;
   for (int s = sg * kSplitWaves + wave; s < p.S; s += p.sgroups * kSplitWaves) {
     const int a = max(p.key_spans[((size_t)i * p.S + s) * 2], 0);
-    const int e = min(p.key_spans[((size_t)i * p.S + s) * 2 + 1], r.pos_max + 1);
+    const int e = min(p.key_spans[((size_t)i * p.S + s) * 2 + 1], pos_max + 1);
     if (e <= a) continue;                          // uniform; mass was zero-filled
-    float acc = 0.0f;
-    stream_keys<D>(p, bt, r.g, j, quarter, qf, a, 16 * kSmGroup, e, r.pos_max, [&](int key0, const f32x4 s4) {
+    float acc[kSplitBlocks];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int key = key0 + 4 * quarter + q;
-        acc += (key < e && key <= pos) ? fast_exp2(s4[q] * c - M) : 0.0f;
-      }
+    for (int nb = 0; nb < kSplitBlocks; ++nb) acc[nb] = 0.0f;
+    stream_keys<D, kSplitBlocks>(p, bt, r[0].g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max,
+                                 [&](int key0, const f32x4 (&sc)[kSplitBlocks]) {
+#pragma unroll
+      for (int nb = 0; nb < kSplitBlocks; ++nb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int key = key0 + 4 * quarter + q;
+          acc[nb] += (key < e && key <= r[nb].pos) ? fast_exp2(sc[nb][q] * c - M[nb]) : 0.0f;
+        }
     });
-    acc += __shfl_xor(acc, 16);
-    acc += __shfl_xor(acc, 32);
-    if (quarter == 0 && r.row_ok) mrow[s] = acc * inv;
+#pragma unroll
+    for (int nb = 0; nb < kSplitBlocks; ++nb) {
+      float v = acc[nb];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      if (quarter == 0 && r[nb].row_ok)
+        p.mass[(((size_t)i * p.P + ps) * p.NQ + (r[nb].slot0 + j)) * p.S + s] = v * inv[nb];
+    }
   }
 }
 
@@ -431,7 +499,7 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
       (reinterpret_cast<uintptr_t>(a->workspace) % 8) == 0) {
     p.stats = static_cast<float2*>(a->workspace);
     p.nsplit = geo.nsplit; p.sgroups = geo.sgroups; p.nq_pad = geo.nq_pad;
-    const unsigned gx = (unsigned)(geo.nq_pad / kSmRows);
+    const unsigned gx = (unsigned)((geo.nq_pad / kSmRows + kSplitBlocks - 1) / kSplitBlocks);
     const dim3 ga(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.nsplit)), gb(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.sgroups));
     if (a->head_dim == 128) {
       hipLaunchKernelGGL(k_span_stats<128>, ga, dim3(kSplitWaves * 64), 0, st, p);
