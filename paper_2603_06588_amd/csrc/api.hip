@@ -88,6 +88,11 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
   if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
     return HOOK_ERR_NULL;
   const Layout l = make_layout(a);
+  // one-dimensional launch grids over the item capacities
+  if (a->dtype == HOOK_BF16 &&
+      (!grid_fits((long long)l.pf_cap * a->num_kv_heads * l.hgroups) ||
+       !grid_fits((long long)l.dec_cap * a->num_kv_heads * l.dec_hgroups)))
+    return HOOK_ERR_UNSUPPORTED;
   if (!a->workspace || a->workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(a->workspace) % kAlign) != 0)
     return HOOK_ERR_WORKSPACE;
 

@@ -388,6 +388,7 @@ template <int D, int HP>
 hipError_t launch_decode_dh(const AttnParams& p, hipStream_t st) {
   const long long grid = (long long)p.dec_cap * p.Hkv * p.dec_hgroups;
   if (grid <= 0) return hipSuccess;
+  if (!grid_fits(grid)) return hipErrorInvalidValue;
   hipLaunchKernelGGL((k_decode<D, HP>), dim3((unsigned)grid), dim3(256), 0, st, p);
   return hipGetLastError();
 }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace hook {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -132,6 +134,23 @@ __device__ __forceinline__ void load_spans(const int* key_spans, int seq, int S,
 }
 
 // launchers (defined next to their kernels); all return hipGetLastError() after the launch
+// The dynamic-LDS limit of a kernel is an attribute per device: it is raised on the first launch
+// on each device (bit per device id in `done`), from whichever host thread gets there first.
+inline hipError_t raise_lds_limit_once(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  if (tracked) done.fetch_or(1ull << dev, std::memory_order_release);
+  return hipSuccess;
+}
+
+// Launch grids are one-dimensional and must fit the 31-bit limit.
+inline bool grid_fits(long long workgroups) { return workgroups >= 0 && workgroups <= 0x7fffffffLL; }
+
 hipError_t launch_plan(const AttnParams& p, hipStream_t st);
 hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st);
 hipError_t launch_prefill128(const AttnParams& p, hipStream_t st);

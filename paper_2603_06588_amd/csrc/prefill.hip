@@ -338,15 +338,12 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
 template <int D>
 hipError_t launch_prefill_d(const AttnParams& p, hipStream_t st) {
   using C = PrefillCfg<D>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<unsigned long long> configured{0};
+  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill<D>), (int)C::LDS_BYTES, configured);
+  if (e != hipSuccess) return e;
   const long long grid = (long long)p.pf_cap * p.Hkv * p.hgroups;
   if (grid <= 0) return hipSuccess;
+  if (!grid_fits(grid)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_prefill<D>, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, p);
   return hipGetLastError();
 }

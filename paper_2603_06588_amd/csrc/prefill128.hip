@@ -550,15 +550,12 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
 }  // namespace
 
 hipError_t launch_prefill128(const AttnParams& p, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill128),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<unsigned long long> configured{0};
+  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill128), kLdsBytes, configured);
+  if (e != hipSuccess) return e;
   const long long grid = (long long)p.pf_cap * p.Hkv * p.hgroups;
   if (grid <= 0) return hipSuccess;
+  if (!grid_fits(grid)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_prefill128, dim3((unsigned)grid), dim3(256), kLdsBytes, st, p);
   return hipGetLastError();
 }
