@@ -134,6 +134,7 @@ extern "C" hook_status hook_capture_qk(const hook_capture_qk_args* a) {
   if (p.P > 0) {
     if (!a->q || !a->cu_q_lens || !a->probe_heads || !a->query_sel || !a->q_out) return HOOK_ERR_NULL;
     const long long chunks = (long long)p.num_seqs * p.P * p.NQ * p.row_chunks;
+    if (!grid_fits((chunks + 255) / 256)) return HOOK_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_capture_q, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
     if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
   }
