@@ -250,6 +250,18 @@ def main() -> int:
                                                   "sample": f"c3_decode_8b: {desc}; {dt:.2f} s"}
         del b3, call3, call3_off
         torch.cuda.empty_cache()
+        # a latency-bound decode step: 8 sequences of 4096 tokens, same heads; what a call costs when
+        # there is too little to stream (planner + decode + combine launches)
+        bs = W.random_batch(7, [4096] * 8, [1] * 8, 32, 8, 128, torch.bfloat16, std=128 ** -0.5,
+                            num_probe_heads=8, max_sel_q=1, max_spans=1, device=dev)
+        calls = binding.call_from_batch(bs, batch_kind=binding.BATCH_DECODE_ONLY)
+        ts = time_call(calls.launch, K, Wm)
+        extra["small_decode_8x4096"] = {
+            "workload": "8 decode rows at 4096 tokens of context, 32 q / 8 kv heads, d 128",
+            "us_per_call": ts["mean_ms"] * 1e3, "kernels_ms": kernel_times(calls, K),
+            "gbs": kv_bytes(bs) / (ts["mean_ms"] * 1e-3) / 1e9}
+        del bs, calls
+        torch.cuda.empty_cache()
 
     if "c4" in only:
         b4 = W.c4_long_prefill_70b(device=dev)

@@ -15,7 +15,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t off_hdr, off_pf, off_dec, off_ord, off_seq, off_part, total;
+  size_t off_hdr, off_pf, off_dec, off_seq, off_part, total;
   int pf_cap, dec_cap, hpw, rows_per_wg, hgroups, dec_hp, dec_hgroups;
 };
 
@@ -49,8 +49,7 @@ Layout make_layout(const hook_attn_probe_args* a) {
   size_t off = 0;
   l.off_hdr = off;  off = align_up(off + sizeof(PlanHeader));
   l.off_pf = off;   off = align_up(off + 2 * sizeof(WorkItem) * (size_t)l.pf_cap);
-  l.off_dec = off;  off = align_up(off + sizeof(WorkItem) * (size_t)l.dec_cap);
-  l.off_ord = off;  off = align_up(off + sizeof(int) * (size_t)l.dec_cap);
+  l.off_dec = off;  off = align_up(off + 2 * sizeof(WorkItem) * (size_t)l.dec_cap);
   l.off_seq = off;  off = align_up(off + sizeof(int2) * (size_t)(a->num_seqs > 0 ? a->num_seqs : 1));
   l.off_part = off;
   off = align_up(off + sizeof(float) * (size_t)l.dec_cap * a->num_q_heads * (a->head_dim + kPartialPad));
@@ -122,7 +121,6 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
   p.pf_cap = l.pf_cap;
   p.dec_items = reinterpret_cast<WorkItem*>(ws + l.off_dec);
   p.dec_cap = l.dec_cap;
-  p.dec_order = reinterpret_cast<int*>(ws + l.off_ord);
   p.seq_dec = reinterpret_cast<int2*>(ws + l.off_seq);
   p.partials = reinterpret_cast<float*>(ws + l.off_part);
   p.hpw = l.hpw; p.rows_per_wg = l.rows_per_wg; p.hgroups = l.hgroups;

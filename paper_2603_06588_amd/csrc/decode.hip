@@ -39,11 +39,13 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   const int rest = bid / p.Hkv;
   const int hg = rest % p.dec_hgroups;
   const int turn = rest / p.dec_hgroups;
+  // the grid covers the whole item capacity, so the turn's records (longest chunks first) can be
+  // fetched together with the item count instead of after it
+  const WorkItem it = p.dec_items[2 * turn];
+  const int slot = p.dec_items[2 * turn + 1].x;
   if (turn >= p.hdr->n_decode) return;
-  // longest chunks are taken first; the clamp only matters if the planner's capacity bound were
-  // ever violated
-  const int item = min(max(p.dec_order[turn], 0), p.dec_cap - 1);
-  const WorkItem it = p.dec_items[item];
+  // the clamp only matters if the planner's capacity bound were ever violated
+  const int item = min(max(slot, 0), p.dec_cap - 1);
   const int seq = it.x, chunk = it.y, L = it.z, qrow = it.w;
   const int CH = p.hdr->chunk_keys;
   const int kstart = chunk * CH;

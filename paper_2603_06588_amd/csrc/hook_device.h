@@ -63,9 +63,8 @@ struct AttnParams {
   PlanHeader* hdr;
   WorkItem* pf_items;
   int pf_cap;
-  WorkItem* dec_items;
+  WorkItem* dec_items;              // two records per turn, longest chunks first: {seq, chunk, L, q row}, {partial slot, -, -, -}
   int dec_cap;
-  int* dec_order;                   // processing order of the decode items: longest chunks first
   int2* seq_dec;                    // per sequence {first decode item, number of chunks}
   float* partials;                  // [dec_cap, Hq, D + kPartialPad]
   // geometry chosen on the host from G

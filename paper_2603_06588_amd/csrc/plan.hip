@@ -189,7 +189,6 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     int2 sd = make_int2(0, 0);
     if (nch > 0 && base + nch <= p.dec_cap) {
       sd = make_int2(base, nch);
-      for (int c = 0; c < nch; ++c) p.dec_items[base + c] = make_int4(i, c, s.L, s.row0);
       atomicAdd(&dhist[(s.L - (nch - 1) * chunk + kBlock - 1) / kBlock], 1);
     }
     // every chunk but the last is full
@@ -260,15 +259,18 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
     for (int i0 = 0; i0 < p.num_seqs; i0 += kPlanThreads) {
       const int i = i0 + tid;
       int2 sd = make_int2(0, 0);
-      int L = 0;
+      int L = 0, qrow = 0;
       if (i == tid) {
         sd = my_sd;
         L = my_s.L;
+        qrow = my_s.row0;
       } else if (i < p.num_seqs) {
         sd = p.seq_dec[i];   // written by this same thread above
         if (sd.y > 0) {
           int dummy = 0;
-          L = read_seq(p, i, &dummy).L;
+          const SeqInfo s = read_seq(p, i, &dummy);
+          L = s.L;
+          qrow = s.row0;
         }
       }
       // the full chunks of all lanes share one bucket: one cursor update per wave
@@ -283,10 +285,15 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
       if (lane == 63 && inc > 0) wbase = atomicAdd(&dhist[chunk / kBlock], inc);
       wbase = __shfl(wbase, 63);
       const int pos = wbase + inc - full;
-      for (int c = 0; c < full; ++c) p.dec_order[pos + c] = sd.x + c;
+      // a turn's records: what the workgroup needs to start, and the slot of its partial result
+      auto put = [&](int turn, int c) {
+        p.dec_items[2 * turn] = make_int4(i, c, L, qrow);
+        p.dec_items[2 * turn + 1] = make_int4(sd.x + c, 0, 0, 0);
+      };
+      for (int c = 0; c < full; ++c) put(pos + c, c);
       if (sd.y > 0) {
         const int len = L - (sd.y - 1) * chunk;
-        p.dec_order[atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1)] = sd.x + sd.y - 1;
+        put(atomicAdd(&dhist[(len + kBlock - 1) / kBlock], 1), sd.y - 1);
       }
     }
   }
