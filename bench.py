@@ -23,8 +23,8 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM traffic per launch (bytes) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
 # (profiles/hbm_traffic_prefill_c2_decode_c3.md).  Set to None whenever the kernel changes.
-TRAFFIC_PREFILL_C2 = 733.1e6
-TRAFFIC_DECODE_C3 = 4913.5e6
+TRAFFIC_PREFILL_C2 = 756.4e6
+TRAFFIC_DECODE_C3 = 4917.2e6
 
 
 def causal_pairs(b) -> int:
