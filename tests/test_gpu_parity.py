@@ -356,3 +356,36 @@ def test_batch_kind_hint():
         else:
             assert torch.equal(bits(call.out[rows]), bits(ref_out[rows]))
             assert torch.equal(bits(call.mass[i]), bits(ref_mass[i]))
+
+
+@pytest.mark.parametrize("group", [0, 1, 2, 3])
+def test_random_valid_batches(group):
+    """Seeded random batches (head geometry, head_dim, dtype, ragged lengths, chunk / single-row / empty
+    sequences, probe set) through the attention entry point and the span pass, against the oracle."""
+    import random
+    from paper_2603_06588_amd import binding
+    rng = random.Random(9000 + group)
+    for it in range(12):
+        G, Hkv = rng.choice([1, 2, 3, 4, 8]), rng.choice([1, 2, 4])
+        d = rng.choice([128, 128, 64])
+        dtype = torch.bfloat16 if rng.random() < 0.85 else torch.float32
+        if dtype == torch.float32:
+            lens = [rng.randint(1, 90) for _ in range(rng.randint(1, 3))]
+        else:
+            lens = [rng.choice([rng.randint(1, 40), rng.randint(41, 300), rng.randint(300, 1200)])
+                    for _ in range(rng.randint(1, 6))]
+        qlens = []
+        for L in lens:
+            r = rng.random()
+            qlens.append(1 if r < 0.35 else L if r < 0.7 else 0 if r < 0.78 else rng.randint(1, L))
+        if sum(qlens) == 0:
+            qlens[0] = 1
+        b = W.random_batch(9100 + 100 * group + it, lens, qlens, G * Hkv, Hkv, d, dtype, std=rng.choice([1.0, 1.0, 0.09]),
+                           num_probe_heads=rng.randint(1, G * Hkv), max_sel_q=rng.choice([1, 2, 5, 33]),
+                           max_spans=rng.randint(1, 8))
+        label = f"random g{group} #{it} lens={lens} q={qlens} Hq={G * Hkv} Hkv={Hkv} d={d} {dtype}"
+        _, _, mass = _check(b, label=label)
+        if dtype == torch.bfloat16:
+            wide = binding.hook_span_mass_batch(b.to(DEV))
+            torch.cuda.synchronize()
+            assert (wide.cpu().double() - mass.cpu().double()).abs().max().item() <= MASS_TOL, label
