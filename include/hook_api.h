@@ -184,6 +184,28 @@ hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* args, int32_t re
 hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits);
 
 /*
+ * Debug aid: checks, on the device, the array CONTENTS that hook_attn_probe cannot verify
+ * without a sync and therefore only makes safe (the conventions at the top of this file), and
+ * returns what it found in *problem_bits (0 = nothing).  Reads the same argument struct; uses
+ * the first 64 bytes of `workspace` (256-byte aligned; the next hook_attn_probe call rewrites
+ * them); launches one small kernel on `stream` and SYNCHRONISES it.  Not a fast path: one
+ * workgroup walks every length, every block id of the live contexts, the probed-head list and
+ * the row selections.  q, k_cache, v_cache, key_spans, out and mass are not touched.
+ */
+typedef enum hook_problem {
+  HOOK_BAD_ROWS_EXCEED_CONTEXT = 1,  /* some n_i > L_i                                        */
+  HOOK_BAD_CONTEXT_TOO_LONG = 2,     /* some L_i > max_blocks_per_seq * block_size            */
+  HOOK_BAD_LENGTH = 4,               /* negative L_i or n_i, cu_q_lens not 0 ... total_q      */
+  HOOK_BAD_BATCH_KIND = 8,           /* a sequence contradicts batch_kind                     */
+  HOOK_BAD_BLOCK_ID = 16,            /* a block id of a live context outside [0, num_blocks)  */
+  HOOK_BAD_PROBE_HEADS = 32,         /* probe_heads not strictly increasing or out of range   */
+  HOOK_BAD_QUERY_SEL = 64            /* a non-empty query_sel range outside [0, n_i) or longer
+                                        than max_sel_q                                        */
+} hook_problem;
+
+hook_status hook_attn_probe_validate(const hook_attn_probe_args* args, int32_t* problem_bits);
+
+/*
  * hidden[t, :] += alpha * vec[:] for every row t with token_mask[t] != 0,
  * computed as one fp32 fused multiply-add per element and rounded to the storage
  * dtype with round-to-nearest-even.  Rows with token_mask[t] == 0 are neither

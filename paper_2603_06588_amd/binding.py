@@ -20,7 +20,7 @@ HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
 EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
-           "hook_attn_probe_device_status", "hook_span_mass", "hook_span_mass_workspace_bytes",
+           "hook_attn_probe_device_status", "hook_attn_probe_validate", "hook_span_mass", "hook_span_mass_workspace_bytes",
            "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
 
@@ -81,6 +81,8 @@ class HookReduceArgs(ctypes.Structure):
 
 REDUCE_SPAN_MEAN, REDUCE_RATIO_MEAN, REDUCE_RATIO_OF_SUMS = 0, 1, 2
 BATCH_MIXED, BATCH_PREFILL_ONLY, BATCH_DECODE_ONLY = 0, 1, 2
+(BAD_ROWS_EXCEED_CONTEXT, BAD_CONTEXT_TOO_LONG, BAD_LENGTH, BAD_BATCH_KIND, BAD_BLOCK_ID, BAD_PROBE_HEADS,
+ BAD_QUERY_SEL) = 1, 2, 4, 8, 16, 32, 64
 
 
 class HookError(RuntimeError):
@@ -112,6 +114,8 @@ def load_library() -> ctypes.CDLL:
         lib.hook_attn_probe_device_status.restype = ctypes.c_int
         lib.hook_attn_probe_device_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
                                                       ctypes.POINTER(ctypes.c_int32)]
+        lib.hook_attn_probe_validate.restype = ctypes.c_int
+        lib.hook_attn_probe_validate.argtypes = [ap, ctypes.POINTER(ctypes.c_int32)]
         lib.hook_steer.restype = ctypes.c_int
         lib.hook_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
@@ -239,6 +243,15 @@ class AttnProbeCall:
                                                           ctypes.byref(bits))
         if st != HOOK_OK:
             raise HookError(st, "hook_attn_probe_device_status")
+        return int(bits.value)
+
+    def validate(self, stream=None) -> int:
+        """Problem bits (HOOK_BAD_*) of the device-resident contents of this call; synchronises."""
+        bits = ctypes.c_int32(0)
+        self.args.stream = _stream_handle(stream)
+        st = load_library().hook_attn_probe_validate(ctypes.byref(self.args), ctypes.byref(bits))
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe_validate")
         return int(bits.value)
 
 

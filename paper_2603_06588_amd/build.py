@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libhook.so")
-SOURCES = ["api.hip", "plan.hip", "prefill.hip", "prefill128.hip", "decode.hip", "attn_f32.hip", "steer.hip", "probes.hip", "capture.hip", "reduce.hip", "residual_steer.hip", "span_mass.hip", "config_json.hip", "kv_write.hip"]
+SOURCES = ["api.hip", "plan.hip", "prefill.hip", "prefill128.hip", "decode.hip", "attn_f32.hip", "steer.hip", "probes.hip", "capture.hip", "reduce.hip", "residual_steer.hip", "span_mass.hip", "config_json.hip", "kv_write.hip", "validate.hip"]
 # packed fp32 instructions are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-inline-asm"]

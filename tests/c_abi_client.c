@@ -22,6 +22,7 @@ int main(void) {
   fails += hook_attn_probe(NULL) != HOOK_ERR_NULL;
   fails += hook_attn_probe(&a) != HOOK_ERR_SHAPE;          /* zero heads */
   fails += hook_attn_probe_workspace_bytes(&a) != 0;
+  fails += hook_attn_probe_validate(NULL, &count) != HOOK_ERR_NULL;
   fails += hook_span_mass(NULL) != HOOK_ERR_NULL;
   fails += hook_span_mass_workspace_bytes(NULL) != 0;
   fails += hook_capture_qk(NULL) != HOOK_ERR_NULL;

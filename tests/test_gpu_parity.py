@@ -322,6 +322,36 @@ def test_many_decode_sequences_take_several_planner_trips():
     _check(b, label="planner_many_decodes")
 
 
+def test_validate_reports_what_the_kernels_only_make_safe():
+    """hook_attn_probe_validate on a clean batch and on one corruption at a time."""
+    from paper_2603_06588_amd import binding as B
+    def bits_of(mutate=None, **kw):
+        b = W.random_batch(195, [300, 77, 150, 40], [300, 1, 90, 0], 8, 2, 128, torch.bfloat16, num_probe_heads=3,
+                           max_sel_q=4, max_spans=2, poison=False).to(DEV)
+        if mutate:
+            mutate(b)
+        return B.call_from_batch(b, **kw).validate()
+    assert bits_of() == 0
+    def rows_exceed(b): b.seq_lens[2] = 50                      # n = 90 > L = 50
+    assert bits_of(rows_exceed) & B.BAD_ROWS_EXCEED_CONTEXT
+    def too_long(b): b.seq_lens[0] = b.block_table.shape[1] * 16 + 1
+    assert bits_of(too_long) & B.BAD_CONTEXT_TOO_LONG
+    def negative(b): b.seq_lens[1] = -3
+    assert bits_of(negative) & B.BAD_LENGTH
+    def bad_prefix(b): b.cu_q_lens[4] = b.total_q - 1           # last entry must equal total_q
+    assert bits_of(bad_prefix) & B.BAD_LENGTH
+    def bad_block(b): b.block_table[0, 3] = 10 ** 6
+    assert bits_of(bad_block) == B.BAD_BLOCK_ID
+    def dead_entry(b): b.block_table[1, b.block_table.shape[1] - 1] = -5   # past the live context: not read
+    assert bits_of(dead_entry) == 0
+    def unsorted(b): b.probe_heads[1] = b.probe_heads[0]
+    assert bits_of(unsorted) == B.BAD_PROBE_HEADS
+    def sel(b): b.query_sel[0, 0], b.query_sel[0, 1] = 298, 302              # reaches past n = 300
+    assert bits_of(sel) == B.BAD_QUERY_SEL
+    assert bits_of(batch_kind=B.BATCH_PREFILL_ONLY) == B.BAD_BATCH_KIND      # sequence 1 is a single row
+    assert bits_of(batch_kind=B.BATCH_DECODE_ONLY) == B.BAD_BATCH_KIND
+
+
 def test_batch_kind_hint():
     """A correct hint changes nothing but the launches; a wrong one drops the contradicting
     sequences (rows untouched, mass zero) and sets bit 3 of the status word."""

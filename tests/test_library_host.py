@@ -163,6 +163,21 @@ def test_rejects_bad_arguments_before_launch(binding):
     assert call(_args(binding, num_seqs=0, total_q=0)) == 0
 
 
+def test_validate_argument_checks(binding):
+    lib = binding.load_library()
+    bits = ctypes.c_int32(7)
+    assert lib.hook_attn_probe_validate(None, ctypes.byref(bits)) == 1
+    a = _args(binding)
+    assert lib.hook_attn_probe_validate(ctypes.byref(a), None) == 1
+    assert lib.hook_attn_probe_validate(ctypes.byref(a), ctypes.byref(bits)) == 1      # null arrays
+    assert bits.value == 0
+    for f in ("block_table", "seq_lens", "cu_q_lens"):
+        setattr(a, f, 4096)
+    assert lib.hook_attn_probe_validate(ctypes.byref(a), ctypes.byref(bits)) == 4      # no workspace
+    a.batch_kind = 5
+    assert lib.hook_attn_probe_validate(ctypes.byref(a), ctypes.byref(bits)) == 2
+
+
 def test_steer_argument_checks(binding):
     lib = binding.load_library()
     assert lib.hook_steer(None, None, 1.0, None, 4, 64, 0, None) == 1
