@@ -31,7 +31,8 @@
  *     call is rejected.  Contents of device arrays (block ids, lengths) cannot be
  *     checked without a sync: block ids outside [0, num_blocks) are clamped so a
  *     bad table cannot fault, lengths beyond the table are clamped, and the
- *     condition is recorded in the workspace (see hook_attn_probe_device_status).
+ *     condition is recorded in the workspace (see hook_attn_probe_device_status;
+ *     hook_attn_probe_validate checks the contents on request).
  *   - One call covers one layer; [layer, head] lists (Section 2, config example)
  *     are split per layer by the caller.
  */
