@@ -71,6 +71,21 @@ typedef enum hook_batch_kind {
   HOOK_BATCH_DECODE_ONLY = 2    /* every n_i is 0 or 1 */
 } hook_batch_kind;
 
+/*
+ * The work lists in the workspace depend only on the batch description (seq_lens, cu_q_lens, the
+ * shape fields and batch_kind), not on q, the caches or the probe arguments, and every layer of a
+ * model step sees the same batch.  HOOK_PLAN_REUSE tells a call that the workspace still holds the
+ * lists a HOOK_PLAN_FRESH call wrote for exactly this batch: the planning kernel is left out.
+ * Because that kernel is also what zero-fills `mass`, a reusing call writes only the entries of
+ * valid selected rows and leaves every other entry of `mass` as it is (give it a zeroed buffer
+ * once; those entries are never written afterwards).  Reusing lists of a different batch is a
+ * caller error that is not detected.
+ */
+typedef enum hook_plan_mode {
+  HOOK_PLAN_FRESH = 0,   /* plan this call (default) */
+  HOOK_PLAN_REUSE = 1    /* the workspace holds the plan of the same batch */
+} hook_plan_mode;
+
 #define HOOK_MAX_SPANS 8      /* S: key spans per sequence (hook_attn_probe) */
 #define HOOK_MAX_SPANS_WIDE 1024  /* S for hook_span_mass and hook_reduce_mass */
 #define HOOK_MAX_SEL_Q 65536  /* NQ: selected query rows per sequence */
@@ -140,6 +155,7 @@ typedef struct hook_attn_probe_args {
 
   /* what the caller knows about the batch (it built cu_q_lens on the host); 0 is always valid */
   int32_t batch_kind;          /* hook_batch_kind */
+  int32_t plan_mode;           /* hook_plan_mode */
 } hook_attn_probe_args;
 
 /*

@@ -37,7 +37,7 @@ class HookAttnProbeArgs(ctypes.Structure):
         ("max_spans", ctypes.c_int32), ("key_spans", ctypes.c_void_p),
         ("out", ctypes.c_void_p), ("mass", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-        ("stream", ctypes.c_void_p), ("batch_kind", ctypes.c_int32),
+        ("stream", ctypes.c_void_p), ("batch_kind", ctypes.c_int32), ("plan_mode", ctypes.c_int32),
     ]
 
 
@@ -81,6 +81,7 @@ class HookReduceArgs(ctypes.Structure):
 
 REDUCE_SPAN_MEAN, REDUCE_RATIO_MEAN, REDUCE_RATIO_OF_SUMS = 0, 1, 2
 BATCH_MIXED, BATCH_PREFILL_ONLY, BATCH_DECODE_ONLY = 0, 1, 2
+PLAN_FRESH, PLAN_REUSE = 0, 1
 (BAD_ROWS_EXCEED_CONTEXT, BAD_CONTEXT_TOO_LONG, BAD_LENGTH, BAD_BATCH_KIND, BAD_BLOCK_ID, BAD_PROBE_HEADS,
  BAD_QUERY_SEL) = 1, 2, 4, 8, 16, 32, 64
 
@@ -180,7 +181,7 @@ class AttnProbeCall:
 
     def __init__(self, q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
                  query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0, out=None, mass=None,
-                 workspace=None, batch_kind: int = 0):
+                 workspace=None, batch_kind: int = 0, plan_mode: int = 0):
         lib = load_library()
         if q.dtype not in _DT:
             raise HookError(3, "hook_attn_probe (dtype)")
@@ -209,6 +210,7 @@ class AttnProbeCall:
         self.workspace = workspace
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel()
         a.batch_kind = int(batch_kind)
+        a.plan_mode = int(plan_mode)
         self.args = a
         self.workspace_needed = need
         self._fn = lib.hook_attn_probe

@@ -352,6 +352,35 @@ def test_validate_reports_what_the_kernels_only_make_safe():
     assert bits_of(batch_kind=B.BATCH_DECODE_ONLY) == B.BAD_BATCH_KIND
 
 
+def test_plan_reuse_across_layers():
+    """One plan per model step: later calls on the same batch (other q / caches / probe arguments)
+    reuse the work lists in the workspace, skip the planner and give the same bits as fresh calls;
+    entries of `mass` that no selected row maps to are left as they were."""
+    from paper_2603_06588_amd import binding as B
+    lens, qlens = [300, 77, 1500, 150, 40, 9], [300, 1, 1, 90, 0, 9]
+    layer0 = W.random_batch(196, lens, qlens, 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=4, max_spans=2).to(DEV)
+    layer1 = W.random_batch(197, lens, qlens, 8, 2, 128, torch.bfloat16, num_probe_heads=5, max_sel_q=4, max_spans=2).to(DEV)
+    fresh0 = B.call_from_batch(layer0)
+    fresh0.launch()
+    want1_out, want1_mass = run_hip(layer1)
+    # the second layer shares layer 0's workspace and block table layout (same lengths), not its tensors
+    marker = 123.25
+    mass1 = torch.full_like(want1_mass, marker)
+    reuse1 = B.call_from_batch(layer1, workspace=fresh0.workspace, mass=mass1, plan_mode=B.PLAN_REUSE)
+    reuse1.out.fill_(float("nan"))
+    times = reuse1.launch_timed()
+    torch.cuda.synchronize()
+    assert times[0] == 0.0                                     # no planner
+    assert torch.equal(bits(reuse1.out[:300]), bits(want1_out[:300]))
+    valid_rows = torch.ones(layer1.total_q, dtype=torch.bool)
+    assert torch.equal(bits(reuse1.out[valid_rows]), bits(want1_out[valid_rows]))
+    written = mass1 != marker
+    assert torch.equal(bits(mass1[written]), bits(want1_mass[written]))
+    assert (want1_mass[~written] == 0).all()                   # what was left alone is what a fresh call zero-fills
+    assert written.any() and (~written).any()
+    assert reuse1.device_status() == 0
+
+
 def test_batch_kind_hint():
     """A correct hint changes nothing but the launches; a wrong one drops the contradicting
     sequences (rows untouched, mass zero) and sets bit 3 of the status word."""

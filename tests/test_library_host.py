@@ -137,6 +137,7 @@ def test_rejects_bad_arguments_before_launch(binding):
     assert call(_args(binding, block_size=32)) == 3
     assert call(_args(binding, dtype=7)) == 3
     assert call(_args(binding, num_seqs=-1)) == 2
+    assert call(_args(binding, plan_mode=2)) == 2
     assert call(_args(binding)) == 1                                      # null tensors
     a = _args(binding, num_probe_heads=2, max_sel_q=1, max_spans=9)
     assert call(a) == 3                                                   # too many spans
