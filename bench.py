@@ -260,11 +260,15 @@ def main() -> int:
                             num_probe_heads=8, max_sel_q=1, max_spans=1, device=dev)
         calls = binding.call_from_batch(bs, batch_kind=binding.BATCH_DECODE_ONLY)
         ts = time_call(calls.launch, K, Wm)
+        calls_reuse = binding.call_from_batch(bs, batch_kind=binding.BATCH_DECODE_ONLY, workspace=calls.workspace,
+                                              plan_mode=binding.PLAN_REUSE)
+        ts_reuse = time_call(calls_reuse.launch, K, Wm)
         extra["small_decode_8x4096"] = {
             "workload": "8 decode rows at 4096 tokens of context, 32 q / 8 kv heads, d 128",
-            "us_per_call": ts["mean_ms"] * 1e3, "kernels_ms": kernel_times(calls, K),
+            "us_per_call": ts["mean_ms"] * 1e3, "us_per_call_plan_reused": ts_reuse["mean_ms"] * 1e3,
+            "kernels_ms": kernel_times(calls, K),
             "gbs": kv_bytes(bs) / (ts["mean_ms"] * 1e-3) / 1e9}
-        del bs, calls
+        del bs, calls, calls_reuse
         torch.cuda.empty_cache()
 
     if "c4" in only:
