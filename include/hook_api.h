@@ -114,6 +114,14 @@ typedef enum hook_plan_mode {
  *                                       over keys max(a,0) .. min(b, pos+1)-1.
  * Entries with no selected row or an empty span (a >= b after clipping) are 0.
  * Spans may overlap; they are independent.
+ *
+ * query_sel[i] is any half-open range of chunk-local row numbers.  It is clipped to the rows
+ * the chunk has, [0, n_i), and to max_sel_q slots: the rows that count are
+ *   t in [max(begin, 0), min(end, n_i, begin + max_sel_q)),
+ * and row t ALWAYS lands in slot t - begin.  So begin < 0 is valid (a range written relative to
+ * a longer prompt of which this chunk holds the tail): the first -begin slots stay 0.  end <=
+ * begin selects nothing.  Every kernel (query chunks, single rows, hook_span_mass,
+ * hook_capture_qk) and hook_reduce_mass follow this one rule.
  */
 typedef struct hook_attn_probe_args {
   /* shapes (host scalars) */
@@ -146,7 +154,9 @@ typedef struct hook_attn_probe_args {
 
   /* outputs (device, caller-allocated) */
   void*  out;                  /* [total_q, Hq, d], dtype as q; rows of skipped sequences untouched */
-  float* mass;                 /* [num_seqs, P, NQ, S] fp32; fully written (zeros where unused) */
+  float* mass;                 /* [num_seqs, P, NQ, S] fp32; fully written (zeros where unused) by a
+                                  HOOK_PLAN_FRESH call; a HOOK_PLAN_REUSE call writes only the entries
+                                  of selected rows (see hook_plan_mode) */
 
   /* scratch (device, caller-allocated, 256-byte aligned) and stream */
   void*  workspace;
@@ -172,6 +182,9 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* args);
  * prefill path; both may be mixed in one call.  Results are deterministic: the
  * same inputs give bit-identical `out` and `mass` on every call, for any
  * physical block permutation, and `out` does not depend on the probe arguments.
+ * HOOK_F32 inputs take one full-precision kernel that needs no work lists: batch_kind and plan_mode
+ * are ignored for them (every valid sequence is computed and `mass` is zero-filled on every call);
+ * the status word is written as for bf16 (bits 0-2).
  */
 hook_status hook_attn_probe(const hook_attn_probe_args* args);
 
@@ -204,8 +217,9 @@ hook_status hook_attn_probe_device_status(const void* workspace, void* stream, i
  * Debug aid: checks, on the device, the array CONTENTS that hook_attn_probe cannot verify
  * without a sync and therefore only makes safe (the conventions at the top of this file), and
  * returns what it found in *problem_bits (0 = nothing).  Reads the same argument struct; uses
- * the first 64 bytes of `workspace` (256-byte aligned; the next hook_attn_probe call rewrites
- * them); launches one small kernel on `stream` and SYNCHRONISES it.  Not a fast path: one
+ * one word of the first 64 bytes of `workspace` (256-byte aligned; a word of its own, so the
+ * status word that hook_attn_probe_device_status reads is left alone); launches one small kernel
+ * on `stream` and SYNCHRONISES it.  Not a fast path: one
  * workgroup walks every length, every block id of the live contexts, the probed-head list and
  * the row selections.  q, k_cache, v_cache, key_spans, out and mass are not touched.
  */
@@ -216,8 +230,10 @@ typedef enum hook_problem {
   HOOK_BAD_BATCH_KIND = 8,           /* a sequence contradicts batch_kind                     */
   HOOK_BAD_BLOCK_ID = 16,            /* a block id of a live context outside [0, num_blocks)  */
   HOOK_BAD_PROBE_HEADS = 32,         /* probe_heads not strictly increasing or out of range   */
-  HOOK_BAD_QUERY_SEL = 64            /* a non-empty query_sel range outside [0, n_i) or longer
-                                        than max_sel_q                                        */
+  HOOK_BAD_QUERY_SEL = 64            /* a query_sel range whose rows inside the chunk do not all fit
+                                        max_sel_q slots (slot = t - begin): rows are dropped.  A
+                                        range that merely reaches outside [0, n_i) is clipped and
+                                        is not reported                                        */
 } hook_problem;
 
 hook_status hook_attn_probe_validate(const hook_attn_probe_args* args, int32_t* problem_bits);
@@ -367,9 +383,10 @@ size_t hook_span_mass_workspace_bytes(const hook_attn_probe_args* args);
  *   HOOK_REDUCE_RATIO_MEAN     scores[i] = sum_p w_p * mean_t a / (a + b)                [num_seqs]
  *   HOOK_REDUCE_RATIO_OF_SUMS  scores[i] = A / (A + B), A = sum_p w_p * mean_t a, B alike [num_seqs]
  * with a = mass[i, p, t, span_a], b = mass[i, p, t, span_b]; a ratio whose denominator is 0
- * counts as 0.  mean_t runs over the rows the probe call selected for sequence i:
- * t in [0, min(query_sel[i,1], n_i, query_sel[i,0] + NQ) - max(query_sel[i,0], 0)), or all NQ
- * rows when query_sel is null; a sequence without selected rows scores 0.  w_p is
+ * counts as 0.  mean_t runs over the slots that hold a row the probe call selected for sequence
+ * i, i.e. slots t - begin for t in [max(begin, 0), min(end, n_i, begin + NQ)) with [begin, end)
+ * = query_sel[i] (leading slots of a negative begin hold no row and do not count), or over all
+ * NQ slots when query_sel is null; a sequence without selected rows scores 0.  w_p is
  * head_weights[p], or 1 / P (the average) when head_weights is null.  With accumulate != 0
  * the result is added to `scores` instead of stored, which sums layers (one call each, the
  * layer weight folded into head_weights) and subtracts a calibration pass (negated weights).

@@ -30,6 +30,23 @@ bool shapes_supported(const hook_attn_probe_args* a) {
   return true;
 }
 
+// Upper bound on the number of decode items the planner can produce, from host scalars only.
+// The planner takes the largest chunk size c in {512, 1024, ..., kMaxChunkKeys} whose item count
+// still gives kDecodeFillWgs workgroups, else 256 keys.  Halving a chunk at most doubles a
+// sequence's item count, so whenever the next larger size was refused (fewer than kDecodeFillWgs
+// workgroups, i.e. at most (kDecodeFillWgs - 1) / wg_per_item items) the chosen size yields at most
+// twice that; and the largest size yields at most one item per kMaxChunkKeys keys of the longest
+// context the block table allows.  (The 256-key tiling of every context is a bound as well.)
+int decode_item_bound(long long num_decode_seqs, long long max_context, int wg_per_item) {
+  const long long refused = 2 * ((kDecodeFillWgs - 1) / wg_per_item);
+  const long long largest = num_decode_seqs * ((max_context + kMaxChunkKeys - 1) / kMaxChunkKeys);
+  const long long finest = num_decode_seqs * ((max_context + 255) / 256);
+  long long cap = refused > largest ? refused : largest;
+  if (cap > finest) cap = finest;
+  if (cap > (1ll << 30)) cap = 1ll << 30;
+  return (int)cap;
+}
+
 Layout make_layout(const hook_attn_probe_args* a) {
   Layout l{};
   const int G = a->num_q_heads / a->num_kv_heads;
@@ -40,11 +57,8 @@ Layout make_layout(const hook_attn_probe_args* a) {
   l.dec_hgroups = G / l.dec_hp;
   if (a->dtype == HOOK_BF16) {
     l.pf_cap = a->total_q / l.rows_per_wg + a->num_seqs;
-    const long long nd = a->num_seqs < a->total_q ? a->num_seqs : a->total_q;
-    const long long per_seq = ((long long)a->max_blocks_per_seq * kBlock + 255) / 256;
-    long long cap = nd * per_seq;
-    if (cap > (1ll << 30)) cap = 1ll << 30;
-    l.dec_cap = (int)cap;
+    l.dec_cap = decode_item_bound(a->num_seqs < a->total_q ? a->num_seqs : a->total_q,
+                                  (long long)a->max_blocks_per_seq * kBlock, a->num_kv_heads * l.dec_hgroups);
   }
   size_t off = 0;
   l.off_hdr = off;  off = align_up(off + sizeof(PlanHeader));
@@ -68,7 +82,8 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* a) {
 
 // Validates, carves the workspace and launches.  With `ev` (5 events) the launches are
 // bracketed by event records so a profiling caller can read per-kernel durations.
-static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev) {
+static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev, void* workspace,
+                                  size_t workspace_bytes) {
   if (!a) return HOOK_ERR_NULL;
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
@@ -93,7 +108,7 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
       (!grid_fits((long long)l.pf_cap * a->num_kv_heads * l.hgroups) ||
        !grid_fits((long long)l.dec_cap * a->num_kv_heads * l.dec_hgroups)))
     return HOOK_ERR_UNSUPPORTED;
-  if (!a->workspace || a->workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(a->workspace) % kAlign) != 0)
+  if (!workspace || workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
     return HOOK_ERR_WORKSPACE;
 
   AttnParams p{};
@@ -116,7 +131,7 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
   p.key_spans = a->key_spans;
   p.out = a->out;
   p.mass = a->mass;
-  char* ws = static_cast<char*>(a->workspace);
+  char* ws = static_cast<char*>(workspace);
   p.hdr = reinterpret_cast<PlanHeader*>(ws + l.off_hdr);
   p.pf_items = reinterpret_cast<WorkItem*>(ws + l.off_pf);
   p.pf_cap = l.pf_cap;
@@ -146,7 +161,10 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev)
   return HOOK_OK;
 }
 
-hook_status hook_attn_probe(const hook_attn_probe_args* a) { return run_attn_probe(a, nullptr); }
+hook_status hook_attn_probe(const hook_attn_probe_args* a) {
+  return a ? run_attn_probe(a, nullptr, a->workspace, a->workspace_bytes) : HOOK_ERR_NULL;
+}
+
 
 hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_ms) {
   if (!kernel_ms) return HOOK_ERR_NULL;
@@ -154,7 +172,7 @@ hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_m
   int made = 0;
   for (; made < 5; ++made)
     if (hipEventCreate(&ev[made]) != hipSuccess) break;
-  hook_status rc = made == 5 ? run_attn_probe(a, ev) : HOOK_ERR_LAUNCH;
+  hook_status rc = made == 5 && a ? run_attn_probe(a, ev, a->workspace, a->workspace_bytes) : HOOK_ERR_LAUNCH;
   if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
     if (hipEventSynchronize(ev[4]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
     for (int i = 0; i < 4 && rc == HOOK_OK; ++i)
@@ -180,7 +198,8 @@ hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* a, int32_t reps,
   for (; made < ev.size(); ++made)
     if (hipEventCreate(&ev[made]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
   // all repetitions are queued before anything is waited for, so the kernels run back to back
-  for (int r = 0; r < reps && rc == HOOK_OK; ++r) rc = run_attn_probe(a, &ev[(size_t)r * 5]);
+  for (int r = 0; r < reps && rc == HOOK_OK; ++r)
+    rc = a ? run_attn_probe(a, &ev[(size_t)r * 5], a->workspace, a->workspace_bytes) : HOOK_ERR_NULL;
   if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
     if (hipEventSynchronize(ev.back()) != hipSuccess) rc = HOOK_ERR_LAUNCH;
     double sum[4] = {0, 0, 0, 0};

@@ -30,8 +30,16 @@ __global__ __launch_bounds__(64) void k_attn_f32(const AttnParams p) {
   const int n = p.cu_q_lens[seq + 1] - row0;
   int L = p.seq_lens[seq];
   const int t = grow - row0;
-  if (t < 0 || t >= n || n > L || L <= 0) return;
+  // the same status bits the planner of the bf16 path records (one lane of the row's first head)
+  if (head == 0 && lane == 0 && t == 0 && n > 0) {
+    int bits = 0;
+    if (L < 0) bits |= kStatNegative;
+    else if (n > min(L, p.max_blocks * kBlock)) bits |= kStatQGtL;
+    if (L > p.max_blocks * kBlock) bits |= kStatLenClamped;
+    if (bits) atomicOr(&p.hdr->status, bits);
+  }
   L = min(L, p.max_blocks * kBlock);
+  if (t < 0 || t >= n || n > L || L <= 0) return;
   const int pos = min(L - n + t, L - 1);
   if (pos < 0) return;
 
@@ -145,7 +153,11 @@ __global__ __launch_bounds__(64) void k_attn_f32(const AttnParams p) {
   }
 }
 
-__global__ __launch_bounds__(256) void k_zero(float* ptr, size_t n) {
+// clears mass and the status word of the workspace header (this path has no planner to do it)
+__global__ __launch_bounds__(256) void k_zero(float* ptr, size_t n, PlanHeader* hdr) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    hdr->n_prefill = 0; hdr->n_decode = 0; hdr->chunk_keys = 0; hdr->status = 0;
+  }
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ptr[i] = 0.0f;
 }
 
@@ -153,10 +165,11 @@ __global__ __launch_bounds__(256) void k_zero(float* ptr, size_t n) {
 
 hipError_t launch_attn_f32(const AttnParams& p, int D, hipStream_t st) {
   const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
-  if (nmass > 0) {
+  {
     size_t blocks = (nmass + 2047) / 2048;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(k_zero, dim3((unsigned)blocks), dim3(256), 0, st, p.mass, nmass);
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_zero, dim3((unsigned)blocks), dim3(256), 0, st, p.mass, nmass, p.hdr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

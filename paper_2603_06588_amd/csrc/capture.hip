@@ -131,17 +131,23 @@ extern "C" hook_status hook_capture_qk(const hook_capture_qk_args* a) {
   p.total_k = a->total_k;
   p.q_out = static_cast<uint4*>(a->q_out); p.k_out = static_cast<uint4*>(a->k_out);
   hipStream_t st = static_cast<hipStream_t>(a->stream);
-  if (p.P > 0) {
+  // every check of both halves comes before the first launch: a rejected call writes nothing
+  const bool do_q = p.P > 0, do_k = p.KH > 0 && p.total_k > 0;
+  const long long chunks = (long long)p.num_seqs * p.P * p.NQ * p.row_chunks;
+  if (do_q) {
     if (!a->q || !a->cu_q_lens || !a->probe_heads || !a->query_sel || !a->q_out) return HOOK_ERR_NULL;
-    const long long chunks = (long long)p.num_seqs * p.P * p.NQ * p.row_chunks;
     if (!grid_fits((chunks + 255) / 256)) return HOOK_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_capture_q, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
-    if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
   }
-  if (p.KH > 0 && p.total_k > 0) {
+  if (do_k) {
     if (!a->k_cache || !a->block_table || !a->seq_lens || !a->capture_kv_heads || !a->cu_k_lens || !a->k_out)
       return HOOK_ERR_NULL;
     if ((long long)kTokTile * p.KH * p.row_chunks > 0x7FFFFFFFll) return HOOK_ERR_UNSUPPORTED;
+  }
+  if (do_q) {
+    hipLaunchKernelGGL(k_capture_q, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, p);
+    if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
+  }
+  if (do_k) {
     hipLaunchKernelGGL(k_capture_k, dim3((unsigned)((p.total_k + kTokTile - 1) / kTokTile)), dim3(256), 0, st, p);
     if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
   }

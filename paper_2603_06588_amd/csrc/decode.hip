@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   bool any_probe = false;
   bool lane_probe = false;
   if (p.P > 0) {
-    const int qb = p.query_sel[2 * seq], qe = p.query_sel[2 * seq + 1];
+    // the single row t = 0 is selected when begin <= 0 < min(end, begin + NQ); its slot is -begin
+    const int qb = p.query_sel[2 * seq], qe = min(p.query_sel[2 * seq + 1], qb + p.NQ);
     any_probe = (qb <= 0 && qe > 0);
     if (any_probe) {
       // is head0 + h probed?  The list is read 64 entries at a time, one per lane, and matched
@@ -378,10 +379,10 @@ __global__ __launch_bounds__(256) void k_combine(const AttnParams p) {
 #pragma unroll
   for (int e = 0; e < D / 64; ++e) og[lane + 64 * e] = (__bf16)(o[e] * inv);
   if (p.P > 0 && lane < p.S) {
-    const int qb = p.query_sel[2 * seq], qe = p.query_sel[2 * seq + 1];
-    if (qb <= 0 && qe > 0) {
+    const int qb = p.query_sel[2 * seq], qe = min(p.query_sel[2 * seq + 1], qb + p.NQ);
+    if (qb <= 0 && qe > 0) {   // row t = 0 sits in slot t - begin, as on every other path
       const int pslot = find_probe_slot(p.probe_heads, p.P, head);
-      if (pslot >= 0) p.mass[(((size_t)seq * p.P + pslot) * p.NQ + 0) * p.S + lane] = a * inv;
+      if (pslot >= 0) p.mass[(((size_t)seq * p.P + pslot) * p.NQ + (-qb)) * p.S + lane] = a * inv;
     }
   }
 }

@@ -21,6 +21,12 @@ constexpr int kTileKeys = 64;       // keys per prefill tile
 constexpr int kWaveRows = 32;       // query rows per prefill wave
 constexpr int kPartialPad = 16;     // floats after the D output values of a decode partial: m, l, a[8], pad
 constexpr int kPlanBuckets = 2048;  // counting-sort buckets (tile counts) of the prefill work list
+// Decode chunking rule shared by the planner (which applies it) and the host (which bounds the
+// number of items it can produce): the largest chunk of 512 << k keys, up to kMaxChunkKeys, that
+// still yields kDecodeFillWgs decode workgroups; 256 keys when none does.
+constexpr int kChunkSizes = 5;
+constexpr int kMaxChunkKeys = 512 << (kChunkSizes - 1);
+constexpr int kDecodeFillWgs = 2048;
 // A running maximum is only raised when a tile's maximum exceeds it by more than this many
 // powers of two; exponentials then stay below 2^kLazyTau, far inside fp32 range, and the
 // normaliser carries the same reference, so the result is the exact softmax.
@@ -33,8 +39,9 @@ struct PlanHeader {
   int n_prefill;   // prefill work items (row blocks)
   int n_decode;    // decode work items (key chunks)
   int chunk_keys;  // keys per decode work item
-  int status;      // kStat* bits
-  int pad[12];
+  int status;      // kStat* bits of the last attention call
+  int problems;    // HOOK_BAD_* bits of the last hook_attn_probe_validate call (a word of its own)
+  int pad[11];
 };
 
 // Work-list records.  prefill: two consecutive records per item,

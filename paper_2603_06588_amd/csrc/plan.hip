@@ -16,8 +16,7 @@ namespace {
 
 constexpr int kPlanThreads = 1024;
 constexpr int kListCap = 1024;   // queued prefill sequences
-constexpr int kChunkSizes = 5;   // candidate decode chunk sizes: 512 << k keys
-constexpr int kDecBuckets = (512 << (kChunkSizes - 1)) / kBlock;   // longest decode chunk in cache blocks
+constexpr int kDecBuckets = kMaxChunkKeys / kBlock;   // longest decode chunk in cache blocks
 
 struct SeqInfo { int L, n, row0, kind; };  // kind: 0 skip, 1 prefill, 2 decode
 
@@ -158,7 +157,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   int chunk = 256;
 #pragma unroll
   for (int k = 0; k < kChunkSizes; ++k)
-    if ((long long)sh_cnt[k] * wg_per_item >= 2048) chunk = 512 << k;
+    if ((long long)sh_cnt[k] * wg_per_item >= kDecodeFillWgs) chunk = 512 << k;
   __syncthreads();
 
   // pass 2: scatter.  What the ordering pass below needs about a thread's first sequence stays

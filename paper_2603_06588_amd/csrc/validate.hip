@@ -28,7 +28,8 @@ __global__ __launch_bounds__(kValThreads) void k_validate(const AttnParams p) {
       bits |= HOOK_BAD_BATCH_KIND;
     if (p.P > 0) {
       const int qb = p.query_sel[2 * i], qe = p.query_sel[2 * i + 1];
-      if (qe > qb && (qb < 0 || qe > n || qe - qb > p.NQ)) bits |= HOOK_BAD_QUERY_SEL;
+      // a range may reach outside the chunk (it is clipped); what loses rows is the NQ cap
+      if (min(qe, n) - max(qb, 0) > 0 && min(qe, n) - qb > p.NQ) bits |= HOOK_BAD_QUERY_SEL;
     }
   }
   if (tid == 0) {
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(kValThreads) void k_validate(const AttnParams p) {
   }
   if (bits) atomicOr(&sh_bits, bits);
   __syncthreads();
-  if (tid == 0) p.hdr->status = sh_bits;
+  if (tid == 0) p.hdr->problems = sh_bits;
 }
 
 }  // namespace
@@ -84,6 +85,6 @@ extern "C" hook_status hook_attn_probe_validate(const hook_attn_probe_args* a, i
   PlanHeader h{};
   if (hipMemcpyAsync(&h, a->workspace, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return HOOK_ERR_LAUNCH;
   if (hipStreamSynchronize(st) != hipSuccess) return HOOK_ERR_LAUNCH;
-  *problem_bits = h.status;
+  *problem_bits = h.problems;
   return HOOK_OK;
 }

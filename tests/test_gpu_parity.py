@@ -16,15 +16,18 @@ def _check(b_cpu, rows=None, label=None, batch_kind=0):
     launch configuration that is timed)."""
     print(f"[case] {label or b_cpu.name} seqs={b_cpu.num_seqs} total_q={b_cpu.total_q}", flush=True)
     b = b_cpu.to(DEV)
-    if batch_kind:
-        from paper_2603_06588_amd import binding
-        call = binding.call_from_batch(b, batch_kind=batch_kind)
-        call.launch()
-        torch.cuda.synchronize()
-        assert call.device_status() == 0
-        out, mass = call.out, call.mass
-    else:
-        out, mass = run_hip(b)
+    from paper_2603_06588_amd import binding
+    # outputs start as NaN: a row or a mass entry that no work item writes cannot pass
+    out = torch.full_like(b.q, float("nan"))
+    mass = torch.full((b.num_seqs, b.num_probe_heads, b.max_sel_q, b.max_spans), float("nan"), dtype=torch.float32,
+                      device=DEV)
+    call = binding.call_from_batch(b, batch_kind=batch_kind, out=out, mass=mass)
+    call.launch()
+    torch.cuda.synchronize()
+    assert call.device_status() == 0
+    written = torch.isfinite(out.float()).all(dim=2).all(dim=1).cpu()
+    from helpers import valid_rows
+    assert bool((written == valid_rows(b_cpu)).all()), f"{label}: rows of out written != rows of valid sequences"
     res = compare_with_oracle(b_cpu, out, mass, rows=rows, label=label or b_cpu.name)
     print(f"       {res}", flush=True)
     return b, out, mass
@@ -94,6 +97,42 @@ def test_all_rows_selected_beyond_4096():
     wide = binding.hook_span_mass_batch(b.to(DEV))
     torch.cuda.synchronize()
     assert (wide.cpu().double() - got).abs().max().item() <= MASS_TOL
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64)])
+def test_query_sel_reaching_outside_the_chunk(dtype, d):
+    """Row ranges that begin before the chunk or end after it, on single-row sequences, query chunks
+    and the span pass: a row keeps slot t - begin, everything else stays zero (the oracle's rule)."""
+    from paper_2603_06588_amd import binding
+    lens, qlens = [500, 300, 64, 130, 90, 77], [1, 1, 64, 130, 1, 1]
+    if dtype == torch.float32:
+        lens, qlens = [90, 60, 33, 70, 20, 41], [1, 1, 33, 70, 1, 1]
+    b = W.random_batch(126, lens, qlens, 8, 2, d, dtype, num_probe_heads=5, max_sel_q=6, max_spans=3)
+    n2, n3 = qlens[2], qlens[3]
+    sel = [[-2, 1], [-5, 3], [-3, 2], [n3 - 2, n3 + 9], [-6, 1], [1, 4]]
+    # seq 0: slot 2; seq 1: slot 5; seq 2: rows 0, 1 in slots 3, 4; seq 3: the last two rows in slots 0, 1;
+    # seq 4: the row would need slot 6 of 6: dropped; seq 5: a range past the only row: nothing
+    b.query_sel[:] = torch.tensor(sel, dtype=torch.int32)
+    _, _, mass = _check(b, label=f"query_sel_outside_{dtype}_{d}")
+    got = mass.cpu()
+    assert (got[0, :, 2] != 0).any() and (got[0, :, :2] == 0).all() and (got[0, :, 3:] == 0).all()
+    assert (got[1, :, 5] != 0).any() and (got[1, :, :5] == 0).all()
+    assert (got[2, :, :3] == 0).all() and (got[2, :, 5:] == 0).all()
+    assert (got[3, :, 2:] == 0).all()
+    assert (got[4] == 0).all() and (got[5] == 0).all()
+    assert n2 > 2
+    # the reductions count exactly the slots that hold a row
+    from oracle.reduce import SPAN_MEAN, reduce_mass
+    _, ref_mass = oracle.attn_probe_batch(b)
+    want = reduce_mass(ref_mass.numpy(), SPAN_MEAN, 0, 1, b.query_sel.tolist(), b.cu_q_lens.tolist())
+    bd = b.to(DEV)
+    scores = binding.hook_reduce_mass(mass, SPAN_MEAN, 0, 1, bd.query_sel, bd.cu_q_lens)
+    torch.cuda.synchronize()
+    assert (scores.cpu().double() - torch.from_numpy(want)).abs().max().item() <= 2e-3
+    if dtype == torch.bfloat16:
+        wide = binding.hook_span_mass_batch(bd)
+        torch.cuda.synchronize()
+        assert (wide.cpu().double() - got.double()).abs().max().item() <= MASS_TOL
 
 
 def test_fp32_small():
@@ -204,14 +243,14 @@ def _sample_rows(b, per_seq: int, seed: int):
     return sorted(rows)
 
 
-def test_c2_full_size_sampled_rows():
+def test_c2_full_size_every_row():
     b = W.c2_prefill_8b()
-    _check(b, rows=_sample_rows(b, 24, 1), label="c2_full", batch_kind=1)
+    _check(b, label="c2_full", batch_kind=1)
 
 
-def test_c2_full_size_peaked_sampled_rows():
+def test_c2_full_size_peaked_every_row():
     b = W.c2_prefill_8b(peaked=True)
-    _check(b, rows=_sample_rows(b, 12, 2), label="c2_full_peaked")
+    _check(b, label="c2_full_peaked")
 
 
 def test_c3_full_size():
@@ -219,14 +258,25 @@ def test_c3_full_size():
     _check(b, label="c3_full", batch_kind=2)
 
 
-def test_c4_full_size_sampled_rows():
-    b = W.c4_long_prefill_70b()
-    _check(b, rows=_sample_rows(b, 40, 3), label="c4_full", batch_kind=1)
+def _stratified_rows(b, block: int, seed: int):
+    """One seeded-random row out of every `block` consecutive rows (every work item of the long
+    prefill is hit), on top of the probed and tile-boundary rows."""
+    gen = torch.Generator().manual_seed(seed)
+    rows = set(_sample_rows(b, 0, seed))
+    for r0 in range(0, b.total_q, block):
+        rows.add(r0 + int(torch.randint(0, min(block, b.total_q - r0), (1,), generator=gen)))
+    return sorted(rows)
 
 
-def test_c5_full_size_sampled_rows():
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c4_full_size_stratified_rows(peaked):
+    b = W.c4_long_prefill_70b(peaked=peaked)
+    _check(b, rows=_stratified_rows(b, 32, 3), label=f"c4_full_peaked{peaked}", batch_kind=1)
+
+
+def test_c5_full_size_every_row():
     b, s = W.c5_mixed()
-    _check(b, rows=_sample_rows(b, 24, 4), label="c5_full")
+    _check(b, label="c5_full")
 
 
 # ---- malformed device-side contents must be made safe, flagged and never fault ----
@@ -346,8 +396,14 @@ def test_validate_reports_what_the_kernels_only_make_safe():
     assert bits_of(dead_entry) == 0
     def unsorted(b): b.probe_heads[1] = b.probe_heads[0]
     assert bits_of(unsorted) == B.BAD_PROBE_HEADS
-    def sel(b): b.query_sel[0, 0], b.query_sel[0, 1] = 298, 302              # reaches past n = 300
+    def clipped(b): b.query_sel[0, 0], b.query_sel[0, 1] = 298, 302          # reaches past n = 300: clipped
+    assert bits_of(clipped) == 0
+    def before(b): b.query_sel[1, 0], b.query_sel[1, 1] = -2, 1              # begins before the chunk: clipped
+    assert bits_of(before) == 0
+    def sel(b): b.query_sel[0, 0], b.query_sel[0, 1] = 290, 300              # 10 rows into 4 slots
     assert bits_of(sel) == B.BAD_QUERY_SEL
+    def sel_neg(b): b.query_sel[1, 0], b.query_sel[1, 1] = -4, 1             # the single row would need slot 4
+    assert bits_of(sel_neg) == B.BAD_QUERY_SEL
     assert bits_of(batch_kind=B.BATCH_PREFILL_ONLY) == B.BAD_BATCH_KIND      # sequence 1 is a single row
     assert bits_of(batch_kind=B.BATCH_DECODE_ONLY) == B.BAD_BATCH_KIND
 

@@ -155,7 +155,7 @@ def test_rejects_bad_arguments_before_launch(binding):
     assert lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding, head_dim=96))) == 0
     assert lib.hook_attn_probe_workspace_bytes(ctypes.byref(_args(binding))) > 0
     # capacities whose launch grid would not fit 31 bits are refused, not truncated
-    a = _args(binding, num_seqs=1 << 20, total_q=1 << 20, max_blocks_per_seq=1 << 16, num_blocks=1 << 20)
+    a = _args(binding, num_seqs=1 << 20, total_q=1 << 20, max_blocks_per_seq=1 << 20, num_blocks=1 << 20)
     for f in ("q", "k_cache", "v_cache", "block_table", "seq_lens", "cu_q_lens", "out"):
         setattr(a, f, 4096)
     a.workspace, a.workspace_bytes = 4096, 1 << 62
