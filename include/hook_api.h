@@ -189,6 +189,31 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* args);
 hook_status hook_attn_probe(const hook_attn_probe_args* args);
 
 /*
+ * hook_attn_probe for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  The same
+ * launches with the same results bit for bit, but the work lists and decode partial results live
+ * in a fixed array of HOOK_STATIC_SCRATCH_BYTES that is part of the library's device image (every
+ * GPU the library runs on holds its own copy until the process ends).  args->workspace and
+ * args->workspace_bytes are ignored; inputs and outputs are still the caller's.  The call makes no
+ * allocation of any kind (no hipMalloc / hipFree, no events, no host containers).
+ *   - A batch whose hook_attn_probe_workspace_bytes() exceeds HOOK_STATIC_SCRATCH_BYTES is
+ *     refused with HOOK_ERR_WORKSPACE before anything is launched (the five reference batches,
+ *     up to 256 decode rows of 8192 tokens or one 32768-row prefill, need under 10 MB).
+ *   - All calls on one GPU share the one array: calls that may overlap in time (different streams,
+ *     different host threads) race on it.  Serialise them, or give the overlapping ones a
+ *     workspace of their own through hook_attn_probe.
+ *   - The array keeps what the last call left.  Nothing in it needs to start at zero: a
+ *     HOOK_PLAN_FRESH call rewrites every word it later reads; HOOK_PLAN_REUSE reuses the lists
+ *     of the previous static call on this GPU and is valid only if that call was for this batch.
+ *   - hook_attn_probe_device_status cannot reach the array; use hook_attn_probe to debug.
+ */
+#define HOOK_STATIC_SCRATCH_BYTES (16u << 20)
+hook_status hook_attn_probe_static(const hook_attn_probe_args* args);
+
+/* HOOK_STATIC_SCRATCH_BYTES of the library that is loaded (host only). */
+size_t hook_attn_probe_static_capacity(void);
+
+/*
  * Profiling aid: the same launches as hook_attn_probe, bracketed by HIP events on
  * args->stream, then WAITS for them.  kernel_ms (HOST pointer, 4 floats) receives the
  * durations in milliseconds of the plan, prefill, decode and combine kernels (fp32

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhook.so")
 HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
-EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
+EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_static", "hook_attn_probe_static_capacity", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
            "hook_attn_probe_device_status", "hook_attn_probe_validate", "hook_span_mass", "hook_span_mass_workspace_bytes",
            "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
 
@@ -107,6 +107,10 @@ def load_library() -> ctypes.CDLL:
         lib.hook_attn_probe_workspace_bytes.argtypes = [ap]
         lib.hook_attn_probe.restype = ctypes.c_int
         lib.hook_attn_probe.argtypes = [ap]
+        lib.hook_attn_probe_static.restype = ctypes.c_int
+        lib.hook_attn_probe_static.argtypes = [ap]
+        lib.hook_attn_probe_static_capacity.restype = ctypes.c_size_t
+        lib.hook_attn_probe_static_capacity.argtypes = []
         lib.hook_attn_probe_timed.restype = ctypes.c_int
         lib.hook_attn_probe_timed.argtypes = [ap, ctypes.POINTER(ctypes.c_float)]
         lib.hook_attn_probe_timed_n.restype = ctypes.c_int
@@ -220,6 +224,13 @@ class AttnProbeCall:
         st = self._fn(ctypes.byref(self.args))
         if st != HOOK_OK:
             raise HookError(st, "hook_attn_probe")
+
+    def launch_static(self, stream=None) -> None:
+        """The same call on the library's own scratch array (the workspace of this object is not used)."""
+        self.args.stream = _stream_handle(stream)
+        st = load_library().hook_attn_probe_static(ctypes.byref(self.args))
+        if st != HOOK_OK:
+            raise HookError(st, "hook_attn_probe_static")
 
     def launch_timed(self, stream=None):
         """Launch, wait, and return the (plan, prefill, decode, combine) kernel times in ms."""

@@ -165,6 +165,40 @@ hook_status hook_attn_probe(const hook_attn_probe_args* a) {
   return a ? run_attn_probe(a, nullptr, a->workspace, a->workspace_bytes) : HOOK_ERR_NULL;
 }
 
+// ---- the same call on the library's own scratch memory ---------------------------------------
+// Work lists and decode partials live in a fixed array in device memory instead of a caller
+// workspace, so the call needs nothing allocated by anybody.  Every GPU holds its own copy of the
+// array at its own address; the host learns that address once per device.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[HOOK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // zero-initialised: address of `scratch` on each device
+
+// Device address of `scratch` on the current device (null on failure).  The array's name is a
+// host-side handle, not an address: only the pointer returned here may be given to kernels.
+void* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // racing threads store the same value
+  return ptr;
+}
+}  // namespace
+
+size_t hook_attn_probe_static_capacity(void) { return (size_t)HOOK_STATIC_SCRATCH_BYTES; }
+
+hook_status hook_attn_probe_static(const hook_attn_probe_args* a) {
+  if (!a) return HOOK_ERR_NULL;
+  // the size check comes first so that an oversized call is refused without touching the device
+  if (shapes_supported(a) && make_layout(a).total > (size_t)HOOK_STATIC_SCRATCH_BYTES) return HOOK_ERR_WORKSPACE;
+  void* ws = scratch_on_current_device();
+  if (!ws) return HOOK_ERR_LAUNCH;
+  return run_attn_probe(a, nullptr, ws, (size_t)HOOK_STATIC_SCRATCH_BYTES);
+}
+
 
 hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_ms) {
   if (!kernel_ms) return HOOK_ERR_NULL;
