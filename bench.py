@@ -22,9 +22,40 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM traffic per launch (bytes) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
-# (profiles/hbm_traffic_prefill_c2_decode_c3.md).  Set to None whenever the kernel changes.
-TRAFFIC_PREFILL_C2 = 756.4e6
-TRAFFIC_DECODE_C3 = 4917.2e6
+# (profiles/hbm_traffic_*.md).  Every figure is tied to the sources of the kernel it was measured on
+# (sha256 over the listed files, first 16 hex digits): once a kernel changes, its figure reads null
+# until the counters are taken again.
+TRAFFIC = {
+    # key: (bytes per launch, source files, hash of those files when the counters were taken)
+}
+
+
+def _source_hash(files) -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(ROOT, "paper_2603_06588_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_for(key: str):
+    """Measured HBM bytes per launch for `key`, or None if the kernel changed since the counter run."""
+    if key not in TRAFFIC:
+        return None
+    nbytes, files, sha = TRAFFIC[key]
+    return nbytes if _source_hash(files) == sha else None
+
+
+def roofline_obj(bound: str, kernel: str, per_launch: float, kernel_ms: float, traffic_key: str = ""):
+    """The roofline record of one kernel: algorithmic flops (mfma) or bytes (hbm) per launch over its
+    measured duration, against the published peak."""
+    if bound == "mfma":
+        achieved, peak, unit, name = per_launch / (kernel_ms * 1e-3) / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s", "flops_per_launch"
+    else:
+        achieved, peak, unit, name = per_launch / (kernel_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s", "bytes_per_launch"
+    return {"bound": bound, "kernel": kernel, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+            "traffic": traffic_for(traffic_key) if traffic_key else None, "kernel_ms": kernel_ms, name: per_launch}
 
 
 def causal_pairs(b) -> int:
@@ -93,8 +124,9 @@ def interleaved_overhead(call_on, call_off, steps: int, warmup: int):
 def kernel_times(call, steps: int):
     """Mean per-kernel durations (ms) over `steps` back-to-back calls, from HIP events recorded inside
     the library around every kernel."""
-    call.launch_timed_n(max(2, steps // 5))      # bring the chip to the state of a timing loop
-    ms = call.launch_timed_n(steps)
+    from paper_2603_06588_amd import benchlib
+    benchlib.launch_timed_n(call, max(2, steps // 5))      # bring the chip to the state of a timing loop
+    ms = benchlib.launch_timed_n(call, steps)
     return dict(zip(("plan_ms", "prefill_ms", "decode_ms", "combine_ms"), ms))
 
 
@@ -135,10 +167,11 @@ def main() -> int:
         return 2
 
     import torch
-    from paper_2603_06588_amd import binding, build as hip_build, workloads as W
-    if not os.path.exists(hip_build.LIB):
+    from paper_2603_06588_amd import benchlib, binding, build as hip_build, workloads as W
+    if not (os.path.exists(hip_build.LIB) and os.path.exists(hip_build.BENCH_LIB)):
         hip_build.build_lib()
     binding.load_library()
+    benchlib.load_library()
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
@@ -202,10 +235,8 @@ def main() -> int:
     flops2 = attn_flops(b2)
     ov2 = interleaved_overhead(call2, call2_off, max(10, K // 2), 3)
     value = flops2 / (t2["mean_ms"] * 1e-3) / 1e12
-    pre_tflops = flops2 / (k2["prefill_ms"] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_prefill128", "achieved": pre_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": pre_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": TRAFFIC_PREFILL_C2,
-                "kernel_ms": k2["prefill_ms"], "flops_per_launch": flops2}
+    roofline = roofline_obj("mfma", "k_prefill128", flops2, k2["prefill_ms"], "k_prefill128/c2")
+    pre_tflops = roofline["achieved"]
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -221,13 +252,10 @@ def main() -> int:
         k3 = kernel_times(call3, K)
         by3 = kv_bytes(b3)
         ov3 = interleaved_overhead(call3, call3_off, max(10, K // 2), 3)
-        dec_gbs = by3 / (k3["decode_ms"] * 1e-3) / 1e9
         extra["decode_c3"] = {
             "workload": "c3_decode_8b", "value": by3 / (t3["mean_ms"] * 1e-3) / 1e9, "unit": "GB/s",
             "ms_per_step": t3["mean_ms"], "median_ms": t3["median_ms"], "min_ms": t3["min_ms"], "kernels_ms": k3,
-            "roofline": {"bound": "hbm", "kernel": "k_decode<128,4>", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
-                         "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_DECODE_C3,
-                         "bytes_per_launch": by3},
+            "roofline": roofline_obj("hbm", "k_decode<128,4>", by3, k3["decode_ms"], "k_decode/c3"),
             "probe_overhead_pct": ov3["overhead_pct"],
             "workspace_mb": call3.workspace_needed / 2**20,
         }
@@ -243,9 +271,8 @@ def main() -> int:
             b3.query_sel, kvh, cu_k, total_k, q_out=q_out, k_out=k_out), K, Wm)
         cap_bytes = 2.0 * (k_out.numel() + q_out.numel()) * k_out.element_size()   # read once + written once
         extra["capture_qk_c3"] = {
-            "workload": "c3_decode_8b, all kv heads", "ms": tcap["mean_ms"], "bytes": cap_bytes,
-            "gbs": cap_bytes / (tcap["mean_ms"] * 1e-3) / 1e9,
-            "frac_of_hbm_peak": cap_bytes / (tcap["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            "workload": "c3_decode_8b, all kv heads", "ms": tcap["mean_ms"],
+            "roofline": roofline_obj("hbm", "k_capture_k (+ k_capture_q)", cap_bytes, tcap["mean_ms"])}
         del q_out, k_out
         if not args.no_cpu_baseline:
             work, dt, desc = oracle_sample(b3, "decode")
@@ -267,7 +294,7 @@ def main() -> int:
             "workload": "8 decode rows at 4096 tokens of context, 32 q / 8 kv heads, d 128",
             "us_per_call": ts["mean_ms"] * 1e3, "us_per_call_plan_reused": ts_reuse["mean_ms"] * 1e3,
             "kernels_ms": kernel_times(calls, K),
-            "gbs": kv_bytes(bs) / (ts["mean_ms"] * 1e-3) / 1e9}
+            "roofline": roofline_obj("hbm", "whole call (plan + k_decode + k_combine)", kv_bytes(bs), ts["mean_ms"])}
         del bs, calls, calls_reuse
         torch.cuda.empty_cache()
 
@@ -283,7 +310,7 @@ def main() -> int:
         extra["long_prefill_c4"] = {
             "workload": "c4_long_prefill_70b", "value": fl4 / (t4["mean_ms"] * 1e-3) / 1e12, "unit": "TFLOP/s",
             "ms_per_step": t4["mean_ms"], "kernels_ms": k4,
-            "frac_of_mfma_peak": fl4 / (k4["prefill_ms"] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+            "roofline": roofline_obj("mfma", "k_prefill128", fl4, k4["prefill_ms"], "k_prefill128/c4"),
             "probe_overhead_pct": ov4["overhead_pct"],
         }
         if not args.no_cpu_baseline:
@@ -333,13 +360,13 @@ def main() -> int:
         t_sum_ms = (fl5 / (PEAK_BF16_MFMA_TFLOPS * 1e12) + by5 / (PEAK_HBM_GBS * 1e9)) * 1e3
         extra["mixed_c5"] = {
             "workload": "c5_mixed", "attn_plus_steer_ms": t5["mean_ms"], "attn_ms": t5a["mean_ms"],
-            "kernels_ms": k5, "prefill_tflops": fl5 / (k5["prefill_ms"] * 1e-3) / 1e12,
-            "decode_gbs": by5 / (k5["decode_ms"] * 1e-3) / 1e9,
+            "kernels_ms": k5,
+            "roofline_prefill": roofline_obj("mfma", "k_prefill128", fl5, k5["prefill_ms"]) if k5["prefill_ms"] > 0 else None,
+            "roofline_decode": roofline_obj("hbm", "k_decode<128,4>", by5, k5["decode_ms"]) if k5["decode_ms"] > 0 else None,
             "roofline_max_ms": t_roof_ms, "roofline_sum_ms": t_sum_ms,
             "probe_overhead_pct": ov5["overhead_pct"],
-            "steer": {"ms": t5s["mean_ms"], "gbs": steer_bytes / (t5s["mean_ms"] * 1e-3) / 1e9,
-                      "frac_of_hbm_peak": steer_bytes / (t5s["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                      "bytes": steer_bytes, "buffers_rotated": 4},
+            "steer": {"ms": t5s["mean_ms"], "buffers_rotated": 4,
+                      "roofline": roofline_obj("hbm", "k_steer_bf16", steer_bytes, t5s["mean_ms"])},
         }
         # steering folded into the residual add that writes hidden: every row read (hidden, delta) and
         # written once, the steered rows cost nothing extra
@@ -361,16 +388,15 @@ def main() -> int:
         tkw = time_call(lambda: binding.hook_kv_write(k_new, v_new, b5.block_table, b5.seq_lens, b5.cu_q_lens,
                                                       b5.k_cache, b5.v_cache), K, Wm)
         kw_bytes = 4.0 * k_new.numel() * k_new.element_size()       # K and V rows read once, written once
-        extra["mixed_c5"]["kv_write"] = {"ms": tkw["mean_ms"], "bytes": kw_bytes,
-                                         "gbs": kw_bytes / (tkw["mean_ms"] * 1e-3) / 1e9}
+        extra["mixed_c5"]["kv_write"] = {"ms": tkw["mean_ms"],
+                                         "roofline": roofline_obj("hbm", "k_kv_write", kw_bytes, tkw["mean_ms"])}
         del k_new, v_new
         t5f = time_call(fused_step, K, Wm)
         t5u = time_call(unfused_step, K, Wm)
         fused_bytes = 3.0 * s5.hidden.numel() * s5.hidden.element_size()
         extra["mixed_c5"]["residual_add_steer"] = {
-            "ms": t5f["mean_ms"], "bytes": fused_bytes, "gbs": fused_bytes / (t5f["mean_ms"] * 1e-3) / 1e9,
-            "frac_of_hbm_peak": fused_bytes / (t5f["mean_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "separate_add_then_steer_ms": t5u["mean_ms"], "buffers_rotated": 4}
+            "ms": t5f["mean_ms"], "separate_add_then_steer_ms": t5u["mean_ms"], "buffers_rotated": 4,
+            "roofline": roofline_obj("hbm", "k_residual_steer_bf16", fused_bytes, t5f["mean_ms"])}
         del deltas
         if not args.no_cpu_baseline:
             b5c, s5c = b5.to("cpu"), s5.to("cpu")
@@ -428,14 +454,14 @@ def main() -> int:
     state_f = {"flops": 0.0}
 
     def mfma_probe():
-        state_f["flops"] = binding.probe_mfma_bf16(32768, 512, sink)
+        state_f["flops"] = benchlib.mfma_bf16(32768, 512, sink)
 
     tm = time_call(mfma_probe, 3, 1)
     big = torch.empty(1 << 32, dtype=torch.uint8, device=dev).fill_(1)
-    tr = time_call(lambda: binding.probe_hbm_read(big, sink), 5, 2)
+    tr = time_call(lambda: benchlib.hbm_read(big, sink), 5, 2)
     sustained = {"mfma_bf16_tflops": state_f["flops"] / (tm["min_ms"] * 1e-3) / 1e12,
                  "hbm_read_gbs": big.numel() / (tr["min_ms"] * 1e-3) / 1e9,
-                 "note": "measured on this box by hook_probe_mfma_bf16 / hook_probe_hbm_read (4 GiB)"}
+                 "note": "measured on this box by hook_bench_mfma_bf16 / hook_bench_hbm_read (4 GiB)"}
     del big
     torch.cuda.empty_cache()
 
@@ -453,6 +479,8 @@ def main() -> int:
                    "ms_graph_replay": t2_graph["mean_ms"], "ms_plan_reused": t2_reuse["mean_ms"]},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "sustained_peaks": sustained,
     }
+    if "long_prefill_c4" in extra:   # the largest single-GPU prefill beside the headline batch
+        line["long_prefill_c4_frac"] = extra["long_prefill_c4"]["roofline"]["frac"]
     line.update(extra)
     print(json.dumps(line))
     return 0

@@ -45,6 +45,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default)   /* the library itself is built with hidden visibility */
+#endif
 
 typedef enum {
   HOOK_OK = 0,
@@ -214,22 +217,6 @@ hook_status hook_attn_probe_static(const hook_attn_probe_args* args);
 size_t hook_attn_probe_static_capacity(void);
 
 /*
- * Profiling aid: the same launches as hook_attn_probe, bracketed by HIP events on
- * args->stream, then WAITS for them.  kernel_ms (HOST pointer, 4 floats) receives the
- * durations in milliseconds of the plan, prefill, decode and combine kernels (fp32
- * inputs: the single attention kernel in kernel_ms[0], the rest 0).  Creates and
- * destroys HIP events; not for graph capture.
- */
-hook_status hook_attn_probe_timed(const hook_attn_probe_args* args, float* kernel_ms);
-
-/*
- * Same, `reps` (1..4096) calls queued back to back before anything is waited for; kernel_ms
- * receives the MEAN duration of each kernel over the repetitions.  This is the steady state a
- * kernel trace of a timing loop sees (a call timed on its own starts on an idle, cooler chip).
- */
-hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* args, int32_t reps, float* kernel_ms);
-
-/*
  * Debug aid: copies the device-side status word of the last hook_attn_probe
  * call that used `workspace` back to the host (this SYNCHRONISES the stream).
  * *status_bits: bit 0 = some n_i > L_i (sequence skipped), bit 1 = some L_i
@@ -295,20 +282,6 @@ hook_status hook_steer(void* hidden, const void* vec, float alpha, const uint8_t
 hook_status hook_residual_add_steer(void* hidden, const void* delta, const void* vec, float alpha,
                                     const uint8_t* token_mask, int32_t num_tokens, int32_t hidden_dim,
                                     int32_t dtype, void* stream);
-
-/*
- * Measurement aids for callers that report roofline fractions (bench.py): what the chip
- * sustains on the two resources the kernels are bound by.  Both launch one kernel on
- * `stream` and return at once; the caller times them.
- *   hook_probe_mfma_bf16  num_workgroups x 4 waves issue independent 32x32x16 bf16 MFMAs back
- *                         to back for `iters` rounds of 16; *flops (HOST) receives the flop
- *                         count of the launch.  `sink` is 4 bytes of device memory (never
- *                         written in practice).
- *   hook_probe_hbm_read   streams `bytes` (multiple of 16, 16-byte aligned) from `src` once
- *                         with 16-byte loads; `sink` as above.
- */
-hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* sink, void* stream, double* flops);
-hook_status hook_probe_hbm_read(const void* src, size_t bytes, void* sink, void* stream);
 
 /*
  * Compact q/k capture: the literal output of the paper's passive hook (Section 2.1, qkv_hook:
@@ -473,6 +446,9 @@ hook_status hook_parse_config_json(const char* text, int32_t* layers, int32_t* h
 const char* hook_status_string(hook_status status);
 int hook_version(void);
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

@@ -19,9 +19,9 @@ LIB_PATH = os.path.join(_HERE, "libhook.so")
 HOOK_OK = 0
 HOOK_BF16, HOOK_F32 = 0, 1
 _DT = {torch.bfloat16: HOOK_BF16, torch.float32: HOOK_F32}
-EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_static", "hook_attn_probe_static_capacity", "hook_attn_probe_timed", "hook_attn_probe_timed_n",
+EXPORTS = ["hook_attn_probe_workspace_bytes", "hook_attn_probe", "hook_attn_probe_static", "hook_attn_probe_static_capacity",
            "hook_attn_probe_device_status", "hook_attn_probe_validate", "hook_span_mass", "hook_span_mass_workspace_bytes",
-           "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_probe_mfma_bf16", "hook_probe_hbm_read", "hook_status_string", "hook_version"]
+           "hook_steer", "hook_residual_add_steer", "hook_kv_write", "hook_capture_qk", "hook_reduce_mass", "hook_parse_layer_heads", "hook_parse_config_json", "hook_status_string", "hook_version"]
 
 
 class HookAttnProbeArgs(ctypes.Structure):
@@ -111,11 +111,6 @@ def load_library() -> ctypes.CDLL:
         lib.hook_attn_probe_static.argtypes = [ap]
         lib.hook_attn_probe_static_capacity.restype = ctypes.c_size_t
         lib.hook_attn_probe_static_capacity.argtypes = []
-        lib.hook_attn_probe_timed.restype = ctypes.c_int
-        lib.hook_attn_probe_timed.argtypes = [ap, ctypes.POINTER(ctypes.c_float)]
-        lib.hook_attn_probe_timed_n.restype = ctypes.c_int
-        lib.hook_attn_probe_timed_n.argtypes = [ctypes.POINTER(HookAttnProbeArgs), ctypes.c_int32,
-                                                ctypes.POINTER(ctypes.c_float)]
         lib.hook_attn_probe_device_status.restype = ctypes.c_int
         lib.hook_attn_probe_device_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
                                                       ctypes.POINTER(ctypes.c_int32)]
@@ -124,11 +119,6 @@ def load_library() -> ctypes.CDLL:
         lib.hook_steer.restype = ctypes.c_int
         lib.hook_steer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
-        lib.hook_probe_mfma_bf16.restype = ctypes.c_int
-        lib.hook_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
-                                             ctypes.POINTER(ctypes.c_double)]
-        lib.hook_probe_hbm_read.restype = ctypes.c_int
-        lib.hook_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.hook_capture_qk.restype = ctypes.c_int
         lib.hook_capture_qk.argtypes = [ctypes.POINTER(HookCaptureQkArgs)]
         lib.hook_kv_write.restype = ctypes.c_int
@@ -231,24 +221,6 @@ class AttnProbeCall:
         st = load_library().hook_attn_probe_static(ctypes.byref(self.args))
         if st != HOOK_OK:
             raise HookError(st, "hook_attn_probe_static")
-
-    def launch_timed(self, stream=None):
-        """Launch, wait, and return the (plan, prefill, decode, combine) kernel times in ms."""
-        self.args.stream = _stream_handle(stream)
-        ms = (ctypes.c_float * 4)()
-        st = load_library().hook_attn_probe_timed(ctypes.byref(self.args), ms)
-        if st != HOOK_OK:
-            raise HookError(st, "hook_attn_probe_timed")
-        return [float(x) for x in ms]
-
-    def launch_timed_n(self, reps: int, stream=None):
-        """`reps` launches back to back; mean (plan, prefill, decode, combine) kernel times in ms."""
-        self.args.stream = _stream_handle(stream)
-        ms = (ctypes.c_float * 4)()
-        st = load_library().hook_attn_probe_timed_n(ctypes.byref(self.args), int(reps), ms)
-        if st != HOOK_OK:
-            raise HookError(st, "hook_attn_probe_timed_n")
-        return [float(x) for x in ms]
 
     def device_status(self, stream=None) -> int:
         bits = ctypes.c_int32(0)
@@ -445,25 +417,6 @@ def probe_heads_for_layer(pairs, layer: int, device="cpu") -> torch.Tensor:
     """Sorted, de-duplicated heads of one layer as the int32 probe_heads tensor of a call."""
     hs = sorted({int(h) for (l, h) in pairs if int(l) == int(layer)})
     return torch.tensor(hs, dtype=torch.int32, device=device)
-
-
-def probe_mfma_bf16(iters: int, num_workgroups: int, sink: torch.Tensor, stream=None) -> float:
-    """Launch the back-to-back MFMA probe; returns the flop count of the launch."""
-    flops = ctypes.c_double(0.0)
-    st = load_library().hook_probe_mfma_bf16(int(iters), int(num_workgroups), _p(sink), _stream_handle(stream),
-                                             ctypes.byref(flops))
-    if st != HOOK_OK:
-        raise HookError(st, "hook_probe_mfma_bf16")
-    return float(flops.value)
-
-
-def probe_hbm_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
-    """Launch the streaming-read probe over `src`; returns the bytes read."""
-    nbytes = src.numel() * src.element_size()
-    st = load_library().hook_probe_hbm_read(_p(src), nbytes, _p(sink), _stream_handle(stream))
-    if st != HOOK_OK:
-        raise HookError(st, "hook_probe_hbm_read")
-    return nbytes
 
 
 def hook_steer(hidden: torch.Tensor, vec: torch.Tensor, alpha: float, token_mask: torch.Tensor,

@@ -5,7 +5,6 @@
 #include "hook_device.h"
 
 #include <cmath>
-#include <vector>
 
 namespace {
 
@@ -80,10 +79,14 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* a) {
   return make_layout(a).total;
 }
 
+}  // extern "C"
+
+namespace hook {
 // Validates, carves the workspace and launches.  With `ev` (5 events) the launches are
-// bracketed by event records so a profiling caller can read per-kernel durations.
-static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev, void* workspace,
-                                  size_t workspace_bytes) {
+// bracketed by event records so a profiling caller can read per-kernel durations (used by the
+// separate measurement library, which links these objects; not part of the exported ABI).
+__attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev,
+                                                                 void* workspace, size_t workspace_bytes) {
   if (!a) return HOOK_ERR_NULL;
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
@@ -160,6 +163,11 @@ static hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev,
   if ((singles && launch_combine(p, a->head_dim, st) != hipSuccess) || !mark(4)) return HOOK_ERR_LAUNCH;
   return HOOK_OK;
 }
+}  // namespace hook
+
+using hook::run_attn_probe;
+
+extern "C" {
 
 hook_status hook_attn_probe(const hook_attn_probe_args* a) {
   return a ? run_attn_probe(a, nullptr, a->workspace, a->workspace_bytes) : HOOK_ERR_NULL;
@@ -199,58 +207,6 @@ hook_status hook_attn_probe_static(const hook_attn_probe_args* a) {
   return run_attn_probe(a, nullptr, ws, (size_t)HOOK_STATIC_SCRATCH_BYTES);
 }
 
-
-hook_status hook_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_ms) {
-  if (!kernel_ms) return HOOK_ERR_NULL;
-  hipEvent_t ev[5];
-  int made = 0;
-  for (; made < 5; ++made)
-    if (hipEventCreate(&ev[made]) != hipSuccess) break;
-  hook_status rc = made == 5 && a ? run_attn_probe(a, ev, a->workspace, a->workspace_bytes) : HOOK_ERR_LAUNCH;
-  if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
-    if (hipEventSynchronize(ev[4]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
-    for (int i = 0; i < 4 && rc == HOOK_OK; ++i)
-      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = HOOK_ERR_LAUNCH;
-    // kernels that the batch_kind hint left out took no time (two events in a row still differ)
-    if (a->dtype == HOOK_BF16 && a->plan_mode == HOOK_PLAN_REUSE) kernel_ms[0] = 0.0f;
-    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_DECODE_ONLY) kernel_ms[1] = 0.0f;
-    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY) kernel_ms[2] = kernel_ms[3] = 0.0f;
-  } else {
-    for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
-  }
-  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
-  return rc;
-}
-
-hook_status hook_attn_probe_timed_n(const hook_attn_probe_args* a, int32_t reps, float* kernel_ms) {
-  if (!kernel_ms) return HOOK_ERR_NULL;
-  if (reps < 1 || reps > 4096) return HOOK_ERR_SHAPE;
-  for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
-  std::vector<hipEvent_t> ev((size_t)reps * 5, nullptr);
-  hook_status rc = HOOK_OK;
-  size_t made = 0;
-  for (; made < ev.size(); ++made)
-    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
-  // all repetitions are queued before anything is waited for, so the kernels run back to back
-  for (int r = 0; r < reps && rc == HOOK_OK; ++r)
-    rc = a ? run_attn_probe(a, &ev[(size_t)r * 5], a->workspace, a->workspace_bytes) : HOOK_ERR_NULL;
-  if (rc == HOOK_OK && a && a->num_seqs > 0 && a->total_q > 0) {
-    if (hipEventSynchronize(ev.back()) != hipSuccess) rc = HOOK_ERR_LAUNCH;
-    double sum[4] = {0, 0, 0, 0};
-    for (int r = 0; r < reps && rc == HOOK_OK; ++r)
-      for (int i = 0; i < 4; ++i) {
-        float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, ev[(size_t)r * 5 + i], ev[(size_t)r * 5 + i + 1]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
-        sum[i] += ms;
-      }
-    for (int i = 0; i < 4; ++i) kernel_ms[i] = (float)(sum[i] / reps);
-    if (a->dtype == HOOK_BF16 && a->plan_mode == HOOK_PLAN_REUSE) kernel_ms[0] = 0.0f;
-    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_DECODE_ONLY) kernel_ms[1] = 0.0f;
-    if (a->dtype == HOOK_BF16 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY) kernel_ms[2] = kernel_ms[3] = 0.0f;
-  }
-  for (size_t i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
-  return rc;
-}
 
 hook_status hook_attn_probe_device_status(const void* workspace, void* stream, int32_t* status_bits) {
   if (!workspace || !status_bits) return HOOK_ERR_NULL;

@@ -1,13 +1,17 @@
-// Measurement aids: what this chip sustains on the two resources the kernels are bound by.
-//   k_probe_mfma  every SIMD issues independent 32x32x16 bf16 MFMAs back to back (two waves
-//                 per SIMD, four accumulators each) - the sustained matrix-core rate, which
-//                 sits below the nominal peak because the clock drops under this load;
-//   k_probe_read  a streaming read of a buffer with 16-byte non-temporal loads - the sustained
-//                 HBM read bandwidth.
-#include "../../include/hook_api.h"
+// Measurement library (libhook_bench.so): everything a benchmark needs beyond the method's own
+// calls, kept out of the product ABI.  It links the same object files as libhook.so, so the
+// kernels it times are the product's kernels.
+//   hook_bench_attn_probe_timed[_n]  the launches of hook_attn_probe bracketed by HIP events
+//   hook_bench_mfma_bf16             what this chip sustains with back-to-back bf16 MFMAs
+//   hook_bench_hbm_read              what it sustains on a streaming read
+#include "../../include/hook_bench.h"
 #include "hook_device.h"
 
+#include <vector>
+
 namespace hook {
+hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev, void* workspace, size_t workspace_bytes);
+
 namespace {
 
 __global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, float* sink) {
@@ -69,12 +73,53 @@ __global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ sr
   if (acc == 0x9E3779B9u) sink[0] = acc;
 }
 
+// kernels that the batch_kind hint or a reused plan left out took no time (two events in a row still differ)
+void zero_skipped(const hook_attn_probe_args* a, float* kernel_ms) {
+  if (a->dtype != HOOK_BF16) return;
+  if (a->plan_mode == HOOK_PLAN_REUSE) kernel_ms[0] = 0.0f;
+  if (a->batch_kind == HOOK_BATCH_DECODE_ONLY) kernel_ms[1] = 0.0f;
+  if (a->batch_kind == HOOK_BATCH_PREFILL_ONLY) kernel_ms[2] = kernel_ms[3] = 0.0f;
+}
+
 }  // namespace
 }  // namespace hook
 
 extern "C" {
 
-hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* sink, void* stream, double* flops) {
+hook_status hook_bench_attn_probe_timed_n(const hook_attn_probe_args* a, int32_t reps, float* kernel_ms) {
+  using namespace hook;
+  if (!a || !kernel_ms) return HOOK_ERR_NULL;
+  if (reps < 1 || reps > 4096) return HOOK_ERR_SHAPE;
+  for (int i = 0; i < 4; ++i) kernel_ms[i] = 0.0f;
+  std::vector<hipEvent_t> ev((size_t)reps * 5, nullptr);
+  hook_status rc = HOOK_OK;
+  size_t made = 0;
+  for (; made < ev.size(); ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
+  // all repetitions are queued before anything is waited for, so the kernels run back to back
+  for (int r = 0; r < reps && rc == HOOK_OK; ++r)
+    rc = run_attn_probe(a, &ev[(size_t)r * 5], a->workspace, a->workspace_bytes);
+  if (rc == HOOK_OK && a->num_seqs > 0 && a->total_q > 0) {
+    if (hipEventSynchronize(ev.back()) != hipSuccess) rc = HOOK_ERR_LAUNCH;
+    double sum[4] = {0, 0, 0, 0};
+    for (int r = 0; r < reps && rc == HOOK_OK; ++r)
+      for (int i = 0; i < 4; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev[(size_t)r * 5 + i], ev[(size_t)r * 5 + i + 1]) != hipSuccess) { rc = HOOK_ERR_LAUNCH; break; }
+        sum[i] += ms;
+      }
+    for (int i = 0; i < 4; ++i) kernel_ms[i] = (float)(sum[i] / reps);
+    zero_skipped(a, kernel_ms);
+  }
+  for (size_t i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
+}
+
+hook_status hook_bench_attn_probe_timed(const hook_attn_probe_args* a, float* kernel_ms) {
+  return hook_bench_attn_probe_timed_n(a, 1, kernel_ms);
+}
+
+hook_status hook_bench_mfma_bf16(int32_t iters, int32_t num_workgroups, void* sink, void* stream, double* flops) {
   if (!sink || !flops) return HOOK_ERR_NULL;
   if (iters <= 0 || num_workgroups <= 0) return HOOK_ERR_SHAPE;
   hipLaunchKernelGGL(hook::k_probe_mfma, dim3((unsigned)num_workgroups), dim3(256), 0,
@@ -85,7 +130,7 @@ hook_status hook_probe_mfma_bf16(int32_t iters, int32_t num_workgroups, void* si
   return HOOK_OK;
 }
 
-hook_status hook_probe_hbm_read(const void* src, size_t bytes, void* sink, void* stream) {
+hook_status hook_bench_hbm_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return HOOK_ERR_NULL;
   if (bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15) != 0) return HOOK_ERR_SHAPE;
   hipLaunchKernelGGL(hook::k_probe_read, dim3(256 * 32), dim3(256), 0, static_cast<hipStream_t>(stream),

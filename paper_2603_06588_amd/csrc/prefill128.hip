@@ -54,11 +54,23 @@ __device__ __forceinline__ void dma16(const void* base, unsigned voff, const voi
                :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 
+// The same load with its address arithmetic folded in: m0 is written first, and the two scalar
+// adds that form the global address (base + 64-bit block offset) fill the wait state that an m0
+// write needs before the load that uses it.
+__device__ __forceinline__ void dma16_at(unsigned base_lo, unsigned base_hi, unsigned off_lo, unsigned off_hi,
+                                         unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\t"
+               "s_add_u32 s98, %1, %3\n\t"
+               "s_addc_u32 s99, %2, %4\n\t"
+               "global_load_lds_dwordx4 %5, s[98:99]"
+               :: "s"(lds_addr), "s"(base_lo), "s"(base_hi), "s"(off_lo), "s"(off_hi), "v"(voff)
+               : "memory", "m0", "s98", "s99", "scc");
+}
+
 struct WaveCtx {
   // loop-invariant per-lane / per-wave values
   unsigned k_read_addr;   // LDS byte offset of this lane's K row with its swizzle term folded in
   unsigned v_read_addr;   // same for the transposed V reads
-  int xor32_addr;         // ds_bpermute address of the lane in the other half holding the same query
   int hf, qi;
   int pos;                // causal horizon of this lane's query row
   float c;                // scale * log2(e)
@@ -66,10 +78,23 @@ struct WaveCtx {
   // direct-to-LDS staging
   const char* kbase;      // k_cache + kv-head offset
   const char* vbase;
+  unsigned kb_lo, kb_hi, vb_lo, vb_hi;   // the same two addresses as 32-bit halves
+  unsigned lds_base;      // LDS address of the K/V buffers
+  unsigned lds_row0;      // byte offset of this wave's first row inside a 16-key block of a tile
+  unsigned blk_units;     // 256-byte units per cache block (all kv heads)
   unsigned blk_bytes;     // bytes per cache block (all kv heads)
   unsigned k_gchunk, v_gchunk;  // per-lane byte offset of the (swizzled) 16-byte chunk inside a row
+  unsigned k_off;         // k_gchunk + this lane's row offset inside a block (loop invariant)
+  unsigned v_row_off;     // this lane's row offset inside a block
   int L, last_blk, w, lane;
 };
+
+// lane l and lane l ^ 32 hold the two key halves of one query: maximum over both (one swap between
+// the lane halves instead of a round trip through LDS)
+__device__ __forceinline__ float half_max(float mx) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // mask (optional) and row maximum of a raw score tile; both lane halves end up with the same value
 template <bool MASK>
@@ -89,9 +114,7 @@ __device__ __forceinline__ float tile_max(const WaveCtx& cx, int key0, f32x16 (&
     m0 = fmaxf(m0, fmaxf(S[0][r], S[0][r + 1]));
     m1 = fmaxf(m1, fmaxf(S[1][r], S[1][r + 1]));
   }
-  const float mx = fmaxf(m0, m1);
-  const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(cx.xor32_addr, __float_as_int(mx)));
-  return fmaxf(mx, other);
+  return half_max(fmaxf(m0, m1));
 }
 
 // Block ids of 64 consecutive blocks (16 tiles) live in one register per lane; two registers
@@ -170,7 +193,8 @@ __device__ __forceinline__ void qk_tile(const WaveCtx& cx, const unsigned char* 
 //            scores of tile kt+1 into Snext (8 slices: 2 MFMAs + 4 exponentials each);
 //   stage D  O += P V of tile kt on the matrix cores while the scalar/vector units issue the
 //            direct-to-LDS loads of V(kt+1) and K(kt+2) and reduce the row maximum of tile
-//            kt+1 (16 slices: 1 MFMA + one piece of the other work each).
+//            kt+1 (16 slices: 1 MFMA + one piece of the other work each); V^T operands are
+//            requested two MFMAs ahead of their use (the first two during stage C).
 // The slices are fenced so the instruction streams stay interleaved as written.  Loads are
 // issued unconditionally with the tile index clamped to the last tile: the buffers they land
 // in are free by then and are never read again.
@@ -205,8 +229,10 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+    if constexpr (PROBE) {
 #pragma unroll
-    for (int s = 0; s < kMaxSpans; ++s) am[s] *= alpha;
+      for (int s = 0; s < kMaxSpans; ++s) am[s] *= alpha;
+    }
   }
   const float m_safe = (m_run == -INFINITY) ? 0.0f : m_run;
   // block-id registers: the K prefetch (two tiles ahead) may enter a new group of 64 blocks
@@ -222,6 +248,7 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
   // -- stage C
   float tsum = 0.0f;
   union PB { uint32_t u[4]; bf16x8 v; } pb[4];
+  bf16x8 va[3];   // ring of V^T operands: requested two matrix instructions ahead of their use
   {
     bf16x8 ka[2][2];
     if constexpr (NEXT) {
@@ -234,6 +261,7 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
         if (s < 7) {
           ka[(s + 1) & 1][0] = read_k(cx, kb, s + 1, 0);
           ka[(s + 1) & 1][1] = read_k(cx, kb, s + 1, 1);
+          __builtin_amdgcn_sched_barrier(0);   // requested a whole slice before their use
         }
         if (s == 0) {
           const f32x16 z = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -244,6 +272,9 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
           Snext[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s & 1][1], qf[s], Snext[1], 0, 0, 0);
         }
       }
+      // the first V^T operands of the P V stage are requested here, two slices before their use
+      if (s == 6) va[0] = read_vt(cx, vb, 0, 0);
+      if (s == 7) va[1] = read_vt(cx, vb, 0, 1);
       // exponentials of elements 4s .. 4s+3 of the current tile
       const int kbk = s >> 2, r0 = 4 * (s & 3);
 #pragma unroll
@@ -298,40 +329,49 @@ __device__ __forceinline__ float tile_iter(const WaveCtx& cx, unsigned char* sme
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_setprio(2);   // the matrix-core-bound stage wins issue arbitration over the other wave
-  bf16x8 va[2];
-  va[0] = read_vt(cx, vb, 0, 0);
+  const unsigned lds_v = cx.lds_base + (2 + ((kt + 1) & 1)) * kTileBytes + cx.lds_row0;   // V(kt+1)
+  const unsigned lds_k = cx.lds_base + (kt & 1) * kTileBytes + cx.lds_row0;               // K(kt+2)
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int m = i >> 2, mb = i & 3;
-    if (i < 15) va[(i + 1) & 1] = read_vt(cx, vb, (i + 1) >> 2, (i + 1) & 3);
-    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i & 1], pb[m].v, O[mb], 0, 0, 0);
+    if (i + 2 < 16) va[(i + 2) % 3] = read_vt(cx, vb, (i + 2) >> 2, (i + 2) & 3);
+    __builtin_amdgcn_sched_barrier(0);
+    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i % 3], pb[m].v, O[mb], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     if (i < 8) {
       if constexpr (NEXT) {   // the last tile of an item has nothing left to fetch
         if (i < 4) {
           // V(kt+1): block offsets were computed when K(kt+1) was issued
-          issue_block<true>(cx, tv, i, cx.vbase, cx.v_gchunk, boff_next[i], Vbuf + ((kt + 1) & 1) * kTileBytes);
+          unsigned off = cx.v_gchunk + cx.v_row_off;
+          if constexpr (MASKNEXT) {   // only a tile that needs the causal mask can reach past the last token
+            const int bidx = min(4 * tv + i, cx.last_blk);
+            const int rmax = cx.L - 1 - 16 * bidx;
+            off = cx.v_gchunk + ((unsigned)min(4 * cx.w + (cx.lane >> 4), rmax) << 8);
+          }
+          dma16_at(cx.vb_lo, cx.vb_hi, (unsigned)boff_next[i], (unsigned)(boff_next[i] >> 32), off,
+                   lds_v + 16 * i * kRowBytes);
         } else {
           const int j = i - 4;
           boff_next[j] = block_offset(cx, sel, tk, j);
-          issue_block<false>(cx, tk, j, cx.kbase, cx.k_gchunk, boff_next[j], Kbuf + (kt & 1) * kTileBytes);
+          dma16_at(cx.kb_lo, cx.kb_hi, (unsigned)boff_next[j], (unsigned)(boff_next[j] >> 32), cx.k_off,
+                   lds_k + 16 * j * kRowBytes);
         }
       }
     } else if constexpr (NEXT) {
       const int q = i - 8;   // scores 4q .. 4q+3 of the next tile
       const int kbk = q >> 2, r0 = 4 * (q & 3);
-      // three-operand maximum written out: fmaxf() would first canonicalise every score with a
-      // v_max of its own; volatile keeps the reduction inside its slice
-      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mx_acc) : "v"(Snext[kbk][r0]), "v"(Snext[kbk][r0 + 1]));
-      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mx_acc) : "v"(Snext[kbk][r0 + 2]), "v"(Snext[kbk][r0 + 3]));
+      // three-operand maxima written out (fmaxf() would first canonicalise every score with a v_max
+      // of its own), both in one statement so that nothing is put between them
+      asm volatile("v_max3_f32 %0, %0, %1, %2\n\tv_max3_f32 %0, %0, %3, %4"
+                   : "+v"(mx_acc)
+                   : "v"(Snext[kbk][r0]), "v"(Snext[kbk][r0 + 1]), "v"(Snext[kbk][r0 + 2]), "v"(Snext[kbk][r0 + 3]));
     }
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_setprio(0);
   float mx_next = 0.0f;
   if constexpr (NEXT) {
-    const float mx = mx_acc;
-    const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(cx.xor32_addr, __float_as_int(mx)));
-    mx_next = fmaxf(mx, other);
+    mx_next = half_max(mx_acc);
   }
   return mx_next;
 }
@@ -434,7 +474,6 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
   const int n_nomask = (wave_pos_min + 1) / kTileKeys;   // tiles whose last key is within every row's horizon
 
   WaveCtx cx;
-  cx.xor32_addr = (lane ^ 32) << 2;
   cx.hf = hf;
   cx.qi = qi;
   cx.pos = L - n + t;
@@ -467,6 +506,12 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
   const int r = 4 * w + (lane >> 4), pc = lane & 15;
   cx.k_gchunk = (unsigned)(pc ^ (r & 15)) * 16;
   cx.v_gchunk = (unsigned)(pc ^ ((r & 3) << 2)) * 16;
+  cx.k_off = cx.k_gchunk + ((unsigned)r << 8);
+  cx.v_row_off = (unsigned)r << 8;
+  cx.kb_lo = (unsigned)(size_t)cx.kbase; cx.kb_hi = (unsigned)((size_t)cx.kbase >> 32);
+  cx.vb_lo = (unsigned)(size_t)cx.vbase; cx.vb_hi = (unsigned)((size_t)cx.vbase >> 32);
+  cx.lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)smem;
+  cx.lds_row0 = (unsigned)(4 * w) * kRowBytes;
 
   bf16x8 qf[8];
   {

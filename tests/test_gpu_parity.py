@@ -424,7 +424,8 @@ def test_plan_reuse_across_layers():
     mass1 = torch.full_like(want1_mass, marker)
     reuse1 = B.call_from_batch(layer1, workspace=fresh0.workspace, mass=mass1, plan_mode=B.PLAN_REUSE)
     reuse1.out.fill_(float("nan"))
-    times = reuse1.launch_timed()
+    from paper_2603_06588_amd import benchlib
+    times = benchlib.launch_timed(reuse1)
     torch.cuda.synchronize()
     assert times[0] == 0.0                                     # no planner
     assert torch.equal(bits(reuse1.out[:300]), bits(want1_out[:300]))
@@ -453,7 +454,8 @@ def test_batch_kind_hint():
         torch.cuda.synchronize()
         assert torch.equal(bits(call.out), bits(ref_out)) and torch.equal(bits(call.mass), bits(ref_mass))
         assert call.device_status() == 0
-        ms = call.launch_timed()
+        from paper_2603_06588_amd import benchlib
+        ms = benchlib.launch_timed(call)
         assert ms[1 if kind == binding.BATCH_DECODE_ONLY else 2] == 0.0     # the other side was not launched
     mixed = W.random_batch(192, [300, 77, 150, 40], [300, 1, 90, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=3,
                            max_sel_q=3, max_spans=2).to(DEV)

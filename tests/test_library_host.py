@@ -43,6 +43,24 @@ def test_exports_every_declared_symbol(binding):
     assert binding.status_string(0) == "ok"
 
 
+def test_measurement_library_exports_its_header_and_the_product_does_not(binding):
+    from paper_2603_06588_amd import benchlib
+    header = open(os.path.join(ROOT, "include", "hook_bench.h")).read()
+    declared = set(re.findall(r"\b(hook_bench_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(benchlib.EXPORTS)
+    lib = benchlib.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    product = binding.load_library()
+    for name in declared:
+        assert not hasattr(product, name), name     # measurement aids stay out of the product ABI
+    # the dynamic symbol table of the product holds the declared calls and nothing else of ours
+    import subprocess
+    syms = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True).stdout
+    ours = {ln.split()[-1] for ln in syms.splitlines() if " T " in ln}
+    assert ours == set(binding.EXPORTS), ours ^ set(binding.EXPORTS)
+
+
 def test_args_struct_matches_header_field_order(binding):
     assert _header_struct_fields("hook_attn_probe_args") == [f[0] for f in binding.HookAttnProbeArgs._fields_]
 
