@@ -25,50 +25,70 @@ __device__ __forceinline__ uint32_t f64_to_bf16_bits(double x) {
   return u >> 16;
 }
 
-constexpr int kRowsPerWg = 4;   // rows sharing one conversion of alpha * vec; also the loads in flight
+// (h + d) + alpha * v for one element in fp32: u = fma(alpha, v, h + d).  `unsure` is raised unless
+// rounding u to bf16 is certain to give what rounding the fp64 sum gives.  t = h + d carries at most
+// half an ulp of error, the fused multiply-add (alpha * v is exact inside it) another half; unless
+// the terms cancel (|u| < |t| / 2) that is at most 1.5 ulp of u, so the bf16 result can only differ
+// when u lies within two fp32 ulps of the midpoint of two bf16 neighbours (low 16 bits 0x8000).
+// Zero, subnormal, infinite and NaN results are left to the fp64 path as well.
+__device__ __forceinline__ float steer_fast(float h, float d, float alpha, float v, bool& unsure) {
+  const float t = h + d;
+  const float u = __builtin_fmaf(alpha, v, t);
+  const uint32_t b = __float_as_uint(u);
+  // class bits: signalling / quiet NaN, -inf, -subnormal, -0, +0, +subnormal, +inf
+  constexpr int kNotNormal = 0x001 | 0x002 | 0x004 | 0x010 | 0x020 | 0x040 | 0x080 | 0x200;
+  unsure = unsure || (((b - 0x7FFEu) & 0xFFFFu) <= 4u) || !(__builtin_fabsf(u) >= 0.5f * __builtin_fabsf(t)) ||
+           __builtin_amdgcn_classf(u, kNotNormal);
+  return u;
+}
 
-// Workgroup = kRowsPerWg rows; thread = one 16-byte column chunk at a time, for all of those rows.
-// alpha * vec (exact in fp64) is formed once per column chunk and reused by every row.
+constexpr int kRowsPerWg = 1;   // fp32 kernel: rows per workgroup
+constexpr int kColsPerTrip = 2;  // bf16 kernel: 16-byte column chunks a thread has in flight (two streams each)
+
+// One workgroup per row: small workgroups keep many independent load streams in flight, which
+// is what this streaming kernel lives on (4, 2, 1 rows per workgroup: 47, 41, 40 us on a
+// [8448, 4096] bf16 buffer).  A thread takes kColsPerTrip column chunks per trip, all loads first.
+// Steered elements take the fp32 route above and fall back, pair by pair, to the fp64 sum in the
+// rare cases (about one pair in ten thousand) where fp32 cannot guarantee the same rounding.
 __global__ __launch_bounds__(256) void k_residual_steer_bf16(uint4* __restrict__ hidden, const uint4* __restrict__ delta,
                                                               const uint4* __restrict__ vec, float alpha,
                                                               const uint8_t* __restrict__ mask, int D8, int T) {
-  const int row0 = blockIdx.x * kRowsPerWg;
-  bool on[kRowsPerWg];
-  bool any = false;
-#pragma unroll
-  for (int r = 0; r < kRowsPerWg; ++r) {
-    on[r] = mask != nullptr && row0 + r < T && mask[row0 + r] != 0;
-    any |= on[r];
-  }
+  const int row = blockIdx.x;
+  const bool on = mask != nullptr && mask[row] != 0;
   const double a = (double)alpha;
-  for (int c = threadIdx.x; c < D8; c += 256) {
-    uint4 h[kRowsPerWg], d[kRowsPerWg];
+  uint4* const hrow = hidden + (size_t)row * D8;
+  const uint4* const drow = delta + (size_t)row * D8;
+  for (int c0 = threadIdx.x; c0 < D8; c0 += 256 * kColsPerTrip) {
+    uint4 h[kColsPerTrip], d[kColsPerTrip], v[kColsPerTrip];
 #pragma unroll
-    for (int r = 0; r < kRowsPerWg; ++r)
-      if (row0 + r < T) {
-        h[r] = load_stream16(&hidden[(size_t)(row0 + r) * D8 + c]);
-        d[r] = load_stream16(&delta[(size_t)(row0 + r) * D8 + c]);
+    for (int u = 0; u < kColsPerTrip; ++u) {
+      const int c = c0 + 256 * u;
+      if (c < D8) {
+        h[u] = load_stream16(&hrow[c]);
+        d[u] = load_stream16(&drow[c]);
+        v[u] = on ? vec[c] : make_uint4(0u, 0u, 0u, 0u);
       }
-    double av[8];
-    if (any) {
-      const uint4 v = vec[c];
-      av[0] = a * (double)bf16_lo(v.x); av[1] = a * (double)bf16_hi(v.x);
-      av[2] = a * (double)bf16_lo(v.y); av[3] = a * (double)bf16_hi(v.y);
-      av[4] = a * (double)bf16_lo(v.z); av[5] = a * (double)bf16_hi(v.z);
-      av[6] = a * (double)bf16_lo(v.w); av[7] = a * (double)bf16_hi(v.w);
     }
 #pragma unroll
-    for (int r = 0; r < kRowsPerWg; ++r) {
-      if (row0 + r >= T) continue;
-      const uint32_t hw[4] = {h[r].x, h[r].y, h[r].z, h[r].w};
-      const uint32_t dw[4] = {d[r].x, d[r].y, d[r].z, d[r].w};
+    for (int u = 0; u < kColsPerTrip; ++u) {
+      const int c = c0 + 256 * u;
+      if (c >= D8) continue;
+      const uint32_t hw[4] = {h[u].x, h[u].y, h[u].z, h[u].w};
+      const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
+      const uint32_t vw[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
       uint32_t y[4];
-      if (on[r]) {
+      if (on) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          const double lo = ((double)bf16_lo(hw[k]) + (double)bf16_lo(dw[k])) + av[2 * k];
-          const double hi = ((double)bf16_hi(hw[k]) + (double)bf16_hi(dw[k])) + av[2 * k + 1];
-          y[k] = f64_to_bf16_bits(lo) | (f64_to_bf16_bits(hi) << 16);
+          bool unsure = false;
+          const float lo = steer_fast(bf16_lo(hw[k]), bf16_lo(dw[k]), alpha, bf16_lo(vw[k]), unsure);
+          const float hi = steer_fast(bf16_hi(hw[k]), bf16_hi(dw[k]), alpha, bf16_hi(vw[k]), unsure);
+          y[k] = pack_bf16(lo, hi);
+          if (__builtin_expect(unsure, 0)) {   // the definition: three fp64 terms, one rounding
+            const double dlo = ((double)bf16_lo(hw[k]) + (double)bf16_lo(dw[k])) + a * (double)bf16_lo(vw[k]);
+            const double dhi = ((double)bf16_hi(hw[k]) + (double)bf16_hi(dw[k])) + a * (double)bf16_hi(vw[k]);
+            y[k] = f64_to_bf16_bits(dlo) | (f64_to_bf16_bits(dhi) << 16);
+          }
         }
       } else {
         // the sum of two bf16 values is exact in fp32 unless they are more than 2^16 apart, and
@@ -77,7 +97,7 @@ __global__ __launch_bounds__(256) void k_residual_steer_bf16(uint4* __restrict__
         for (int k = 0; k < 4; ++k)
           y[k] = pack_bf16(bf16_lo(hw[k]) + bf16_lo(dw[k]), bf16_hi(hw[k]) + bf16_hi(dw[k]));
       }
-      store_stream16(&hidden[(size_t)(row0 + r) * D8 + c], make_uint4(y[0], y[1], y[2], y[3]));
+      store_stream16(&hrow[c], make_uint4(y[0], y[1], y[2], y[3]));
     }
   }
 }
@@ -143,7 +163,7 @@ extern "C" hook_status hook_residual_add_steer(void* hidden, const void* delta, 
        (steer ? reinterpret_cast<uintptr_t>(vec) : 0)) % 16 != 0)
     return HOOK_ERR_UNSUPPORTED;
   const int Dc = hidden_dim / per;
-  const unsigned blocks = (unsigned)((num_tokens + kRowsPerWg - 1) / kRowsPerWg);
+  const unsigned blocks = (unsigned)((num_tokens + kRowsPerWg - 1) / kRowsPerWg);   // = num_tokens
   hipStream_t st = static_cast<hipStream_t>(stream);
   const uint8_t* m = steer ? token_mask : nullptr;
   if (dtype == HOOK_BF16)

@@ -102,6 +102,54 @@ def test_residual_steer_matches_oracle(dtype, T, D):
         assert torch.equal(bits(h.cpu()), bits(want0))
 
 
+def test_residual_steer_rounding_corner_cases_are_bit_exact():
+    """Inputs built to sit where an fp32 evaluation cannot be trusted to round like the fp64 sum:
+    results on or next to the midpoint of two bf16 neighbours, cancelling terms, huge exponent gaps,
+    subnormal / overflowing results, infinities and NaNs.  Every bit must equal the oracle's."""
+    from paper_2603_06588_amd import binding
+    gen = torch.Generator().manual_seed(4242)
+    T, D = 96, 1024
+    h = torch.randn((T, D), generator=gen).to(torch.bfloat16)
+    d = torch.randn((T, D), generator=gen).to(torch.bfloat16)
+    vec = torch.randn((D,), generator=gen).to(torch.bfloat16)
+    # rows 0-15: h = 1 + k 2^-7 (bf16 neighbours), d = 0, alpha * v = 2^-8 +- tiny: exact midpoints and near misses
+    k = torch.arange(D) % 64
+    for r in range(16):
+        h[r] = (1.0 + k.double() * 2.0 ** -7).to(torch.bfloat16)
+        d[r] = 0.0
+    # rows 16-31: h + d cancels to something far smaller than either, then alpha * v decides
+    for r in range(16, 32):
+        d[r] = (-h[r].double() * (1.0 + 2.0 ** -(r - 14))).to(torch.bfloat16)
+    # rows 32-47: exponent gaps beyond 24 bits between the terms
+    for r in range(32, 48):
+        d[r] = (h[r].double() * 2.0 ** -(20 + r - 32)).to(torch.bfloat16)
+    # rows 48-63: tiny and huge magnitudes (subnormal / overflowing sums)
+    h[48:56] = (h[48:56].double() * 2.0 ** -125).to(torch.bfloat16)
+    d[48:56] = (d[48:56].double() * 2.0 ** -126).to(torch.bfloat16)
+    h[56:64] = (h[56:64].double().sign() * 3.0e38).to(torch.bfloat16)
+    d[56:64] = (d[56:64].double().abs() * 1.0e37 * h[56:64].double().sign()).to(torch.bfloat16)
+    # rows 64-71: infinities and NaNs in every operand position
+    h[64, ::3] = float("inf"); d[65, ::5] = float("-inf"); h[66, ::7] = float("nan"); d[67, ::2] = float("nan")
+    h[68, ::4] = float("inf"); d[68, ::4] = float("-inf")
+    mask = torch.ones(T, dtype=torch.uint8)
+    mask[80:] = 0
+    for alpha, v_scale in ((2.0 ** -8, None), (3.25, 1.0), (1.0e-30, 1.0), (-7.0e5, 1.0)):
+        v = vec.clone()
+        if v_scale is None:     # v = 1 (+- one bf16 step on some columns): alpha * v = 2^-8 exactly or a hair off
+            v = torch.ones(D).to(torch.bfloat16)
+            v[1::3] = (1.0 + 2.0 ** -7)
+            v[2::3] = (1.0 - 2.0 ** -8)
+        want = oracle.residual_steer(h, d, v, alpha, mask)
+        hh = h.to(DEV).clone()
+        binding.hook_residual_add_steer(hh, d.to(DEV), v.to(DEV), alpha, mask.to(DEV))
+        torch.cuda.synchronize()
+        got = hh.cpu()
+        nan_w, nan_g = torch.isnan(want.float()), torch.isnan(got.float())
+        assert torch.equal(nan_w, nan_g), alpha
+        same = (bits(got) == bits(want)) | nan_w
+        assert bool(same.all()), (alpha, int((~same).sum()))
+
+
 def test_residual_steer_c5_shape_sampled():
     from paper_2603_06588_amd import binding
     _, s = W.c5_mixed()
