@@ -25,7 +25,9 @@
  * Pins (tests/test_oracle_pins.py): brute force on tiny inputs, row sums equal
  * one, closed form for Q = 0, dominant-key limit, torch fp64 softmax(QK^T)V on
  * un-paged tensors, paging permutation invariance, chunked-prefill positions,
- * GQA replication, steering special cases.  Every function below is pinned.
+ * GQA replication, steering special cases; for the 8-bit cache: the 256-entry
+ * decoding table against a library's, and equality with the 16-bit path on caches
+ * whose dequantised values bf16 holds exactly.  Every function below is pinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -35,7 +37,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
+enum { ORACLE_BF16 = 0, ORACLE_F32 = 1, ORACLE_FP8_E4M3 = 2 };
 
 int hook_oracle_num_threads(void) {
 #ifdef _OPENMP
@@ -45,9 +47,28 @@ int hook_oracle_num_threads(void) {
 #endif
 }
 
+/*
+ * One byte of an 8-bit floating-point cache -> double, exactly.  The format is the 8-bit
+ * "E4M3" interchange format (1 sign, 4 exponent, 3 mantissa bits, bias 7, no infinities, the one
+ * NaN pattern S.1111.111): value = (-1)^S * 2^(E-7) * (1 + M/8) for E > 0 and
+ * (-1)^S * 2^-6 * M/8 for E = 0.
+ */
+static double load_fp8_e4m3(uint8_t b) {
+  const int sign = b >> 7, E = (b >> 3) & 15, M = b & 7;
+  double v;
+  if (E == 15 && M == 7) return NAN;
+  if (E == 0) v = ldexp((double)M / 8.0, -6);
+  else v = ldexp(1.0 + (double)M / 8.0, E - 7);
+  return sign ? -v : v;
+}
+
+/* Exposed so a test can pin the 256-entry decoding table on its own. */
+double hook_oracle_fp8_e4m3_value(uint8_t b) { return load_fp8_e4m3(b); }
+
 /* Stored element -> double, exactly (bf16 is the top half of an IEEE float). */
 static double load_elem(const void* base, size_t idx, int dtype) {
   if (dtype == ORACLE_F32) return (double)((const float*)base)[idx];
+  if (dtype == ORACLE_FP8_E4M3) return load_fp8_e4m3(((const uint8_t*)base)[idx]);
   uint32_t bits = ((uint32_t)((const uint16_t*)base)[idx]) << 16;
   float f;
   memcpy(&f, &bits, sizeof f);
@@ -91,16 +112,18 @@ static uint16_t double_to_bf16_rne(double x) {
  * in `out` is left untouched.  `mass` is zero-filled first.
  * Returns 0, or a negative code for malformed arguments.
  */
-int hook_oracle_attn_probe(
+static int attn_probe_impl(
     int num_seqs, int total_q, int Hq, int Hkv, int d, int B, int max_blocks, int num_blocks,
     int dtype, double scale,
     const void* q, const void* k_cache, const void* v_cache,
     const int32_t* block_table, const int32_t* seq_lens, const int32_t* cu_q_lens,
     int P, const int32_t* probe_heads, int NQ, const int32_t* query_sel, int S, const int32_t* key_spans,
     int n_rows, const int32_t* rows,
+    int kv_dtype, const float* k_scale, const float* v_scale,
     double* out, double* mass) {
   if (Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || B <= 0) return -1;
   if (dtype != ORACLE_BF16 && dtype != ORACLE_F32) return -2;
+  if (kv_dtype != dtype && kv_dtype != ORACLE_FP8_E4M3) return -2;
   const int G = Hq / Hkv;
   if (mass && P > 0) memset(mass, 0, sizeof(double) * (size_t)num_seqs * P * NQ * S);
   int bad = 0;
@@ -137,8 +160,11 @@ int hook_oracle_attn_probe(
         if (blk < 0 || blk >= num_blocks) { ok = 0; break; }
         const size_t base = (((size_t)blk * Hkv + g) * B + (size_t)(j % B)) * d;
         for (int c = 0; c < d; ++c) {
-          Kd[(size_t)j * d + c] = load_elem(k_cache, base + c, dtype);
-          Vd[(size_t)j * d + c] = load_elem(v_cache, base + c, dtype);
+          Kd[(size_t)j * d + c] = load_elem(k_cache, base + c, kv_dtype);
+          Vd[(size_t)j * d + c] = load_elem(v_cache, base + c, kv_dtype);
+          /* a quantised cache stores value / scale: one scale per kv head */
+          if (k_scale) Kd[(size_t)j * d + c] *= (double)k_scale[g];
+          if (v_scale) Vd[(size_t)j * d + c] *= (double)v_scale[g];
         }
       }
       if (!ok) { bad = 1; free(Kd); free(Vd); free(s); free(qd); free(od); continue; }
@@ -192,6 +218,39 @@ int hook_oracle_attn_probe(
   }
   free(want);
   return bad ? -3 : 0;
+}
+
+int hook_oracle_attn_probe(
+    int num_seqs, int total_q, int Hq, int Hkv, int d, int B, int max_blocks, int num_blocks,
+    int dtype, double scale,
+    const void* q, const void* k_cache, const void* v_cache,
+    const int32_t* block_table, const int32_t* seq_lens, const int32_t* cu_q_lens,
+    int P, const int32_t* probe_heads, int NQ, const int32_t* query_sel, int S, const int32_t* key_spans,
+    int n_rows, const int32_t* rows,
+    double* out, double* mass) {
+  return attn_probe_impl(num_seqs, total_q, Hq, Hkv, d, B, max_blocks, num_blocks, dtype, scale, q, k_cache, v_cache,
+                         block_table, seq_lens, cu_q_lens, P, probe_heads, NQ, query_sel, S, key_spans, n_rows, rows,
+                         dtype, NULL, NULL, out, mass);
+}
+
+/*
+ * The same definition over an 8-bit (E4M3) key/value cache: every cache byte is first turned back
+ * into the number it stands for, K[j][c] = value(byte) * k_scale[g] (V alike, one fp32 scale per kv
+ * head), then everything is as above.  q keeps its own dtype.  This is the "dequantise, then the
+ * plain definition" reading of a quantised cache; the paper does not discuss cache precision.
+ */
+int hook_oracle_attn_probe_kv8(
+    int num_seqs, int total_q, int Hq, int Hkv, int d, int B, int max_blocks, int num_blocks,
+    int dtype, double scale,
+    const void* q, const void* k_cache, const void* v_cache, const float* k_scale, const float* v_scale,
+    const int32_t* block_table, const int32_t* seq_lens, const int32_t* cu_q_lens,
+    int P, const int32_t* probe_heads, int NQ, const int32_t* query_sel, int S, const int32_t* key_spans,
+    int n_rows, const int32_t* rows,
+    double* out, double* mass) {
+  if (!k_scale || !v_scale) return -1;
+  return attn_probe_impl(num_seqs, total_q, Hq, Hkv, d, B, max_blocks, num_blocks, dtype, scale, q, k_cache, v_cache,
+                         block_table, seq_lens, cu_q_lens, P, probe_heads, NQ, query_sel, S, key_spans, n_rows, rows,
+                         ORACLE_FP8_E4M3, k_scale, v_scale, out, mass);
 }
 
 /*

@@ -45,6 +45,11 @@ def _load():
         lib.hook_oracle_attn_probe.restype = i32
         lib.hook_oracle_attn_probe.argtypes = [i32] * 9 + [dbl] + [vp] * 6 + [i32, vp, i32, vp, i32, vp,
                                                                          i32, vp, vp, vp]
+        lib.hook_oracle_attn_probe_kv8.restype = i32
+        lib.hook_oracle_attn_probe_kv8.argtypes = [i32] * 9 + [dbl] + [vp] * 8 + [i32, vp, i32, vp, i32, vp,
+                                                                             i32, vp, vp, vp]
+        lib.hook_oracle_fp8_e4m3_value.restype = dbl
+        lib.hook_oracle_fp8_e4m3_value.argtypes = [ctypes.c_uint8]
         lib.hook_oracle_steer.restype = i32
         lib.hook_oracle_steer.argtypes = [vp, vp, ctypes.c_float, vp, i32, i32, i32, vp]
         lib.hook_oracle_residual_steer.restype = i32
@@ -71,17 +76,28 @@ def _ptr(t: Optional[torch.Tensor]):
     return ctypes.c_void_p(t.data_ptr()) if t is not None and t.numel() > 0 else ctypes.c_void_p(0)
 
 
+def fp8_e4m3_value(byte: int) -> float:
+    """The number an 8-bit E4M3 cache byte stands for (NaN for the one NaN pattern per sign)."""
+    return float(_load().hook_oracle_fp8_e4m3_value(int(byte) & 0xFF))
+
+
 def attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q,
                query_sel, max_spans, key_spans, scale: float,
-               rows: Optional[Sequence[int]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+               rows: Optional[Sequence[int]] = None, k_scale=None, v_scale=None) -> Tuple[torch.Tensor, torch.Tensor]:
     """Return (out fp64 [total_q, Hq, d], mass fp64 [num_seqs, P, NQ, S]).
 
     ``rows`` restricts the computation to the given global query rows; other rows
     of ``out`` come back as NaN so an accidental comparison cannot pass.
+    uint8 caches are 8-bit E4M3 bytes and need ``k_scale`` / ``v_scale`` ([Hkv] fp32).
     """
     lib = _load()
     q, k_cache, v_cache = _cpu(q), _cpu(k_cache), _cpu(v_cache)
-    assert q.dtype in _DT and k_cache.dtype == q.dtype and v_cache.dtype == q.dtype
+    kv8 = k_cache.dtype == torch.uint8
+    assert q.dtype in _DT and v_cache.dtype == k_cache.dtype and (kv8 or k_cache.dtype == q.dtype)
+    if kv8:
+        assert k_scale is not None and v_scale is not None
+        k_scale, v_scale = _cpu(k_scale, torch.float32), _cpu(v_scale, torch.float32)
+        assert k_scale.numel() == k_cache.shape[1] and v_scale.numel() == k_cache.shape[1]
     block_table = _cpu(block_table, torch.int32)
     seq_lens = _cpu(seq_lens, torch.int32)
     cu_q_lens = _cpu(cu_q_lens, torch.int32)
@@ -98,13 +114,17 @@ def attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_head
     rows_t = None
     if rows is not None:
         rows_t = torch.tensor(list(rows), dtype=torch.int32)
-    rc = lib.hook_oracle_attn_probe(
-        num_seqs, total_q, Hq, Hkv, d, B, max_blocks, num_blocks, _DT[q.dtype], float(scale),
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(seq_lens), _ptr(cu_q_lens),
-        P, _ptr(probe_heads), NQ, _ptr(query_sel), S, _ptr(key_spans),
-        0 if rows_t is None else int(rows_t.numel()),
-        ctypes.c_void_p(rows_t.data_ptr()) if rows_t is not None else ctypes.c_void_p(0),
-        _ptr(out), _ptr(mass))
+    tail = (P, _ptr(probe_heads), NQ, _ptr(query_sel), S, _ptr(key_spans),
+            0 if rows_t is None else int(rows_t.numel()),
+            ctypes.c_void_p(rows_t.data_ptr()) if rows_t is not None else ctypes.c_void_p(0),
+            _ptr(out), _ptr(mass))
+    head = (num_seqs, total_q, Hq, Hkv, d, B, max_blocks, num_blocks, _DT[q.dtype], float(scale))
+    if kv8:
+        rc = lib.hook_oracle_attn_probe_kv8(*head, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                                            _ptr(block_table), _ptr(seq_lens), _ptr(cu_q_lens), *tail)
+    else:
+        rc = lib.hook_oracle_attn_probe(*head, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                        _ptr(seq_lens), _ptr(cu_q_lens), *tail)
     if rc != 0:
         raise ValueError(f"hook_oracle_attn_probe rejected its arguments (code {rc})")
     return out, mass
@@ -113,7 +133,8 @@ def attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_head
 def attn_probe_batch(b, rows: Optional[Sequence[int]] = None):
     """Same, taking any object with the batch attributes (duck-typed, nothing imported)."""
     return attn_probe(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads,
-                      b.max_sel_q, b.query_sel, b.max_spans, b.key_spans, b.scale, rows=rows)
+                      b.max_sel_q, b.query_sel, b.max_spans, b.key_spans, b.scale, rows=rows,
+                      k_scale=getattr(b, "k_scale", None), v_scale=getattr(b, "v_scale", None))
 
 
 def steer(hidden: torch.Tensor, vec: torch.Tensor, alpha: float, token_mask: torch.Tensor) -> torch.Tensor:

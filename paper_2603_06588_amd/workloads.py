@@ -54,6 +54,9 @@ class AttnBatch:
     key_spans: torch.Tensor           # int32 [num_seqs, S, 2] absolute [start, end)
     seed: int = 0
     notes: dict = field(default_factory=dict)
+    # 8-bit cache variant (k_cache / v_cache are uint8 E4M3 bytes): one fp32 scale per kv head
+    k_scale: Optional[torch.Tensor] = None
+    v_scale: Optional[torch.Tensor] = None
 
     @property
     def num_probe_heads(self) -> int:
@@ -74,6 +77,50 @@ class AttnBatch:
         kw = dict(self.__dict__)
         kw["probe_heads"] = self.probe_heads[:0].clone()
         return AttnBatch(**kw)
+
+
+FP8_NAN_BYTE = 0x7F            # the NaN pattern of the 8-bit E4M3 format
+_FP8_BYTE_RMS = 3.9            # root mean square of the numbers the bytes drawn below stand for
+
+
+def fp8_cache_variant(b: AttnBatch, seed: int, k_std: float = 1.0, v_std: float = 1.0,
+                      pow2_scales: bool = False) -> AttnBatch:
+    """The same batch with an 8-bit (E4M3) key/value cache of the same shape.
+
+    Bytes are drawn directly (no quantisation arithmetic here): sign and mantissa bits uniform,
+    exponent field triangular over 4..10, so the stored numbers span 1/8 .. 15 with a root mean
+    square of about 3.9; the per-kv-head scales are chosen so that keys / values have roughly the
+    requested standard deviation (exact powers of two when ``pow2_scales``).  Slots that were
+    poisoned with NaN in the 16-bit cache hold the format's NaN byte.
+    """
+    gen = torch.Generator().manual_seed(seed)
+    shape = tuple(b.k_cache.shape)
+    Hkv = b.num_kv_heads
+
+    def draw():
+        sign = torch.randint(0, 2, shape, generator=gen, dtype=torch.int32)
+        expo = 4 + torch.randint(0, 4, shape, generator=gen, dtype=torch.int32) + torch.randint(0, 4, shape, generator=gen, dtype=torch.int32)
+        mant = torch.randint(0, 8, shape, generator=gen, dtype=torch.int32)
+        return ((sign << 7) | (expo << 3) | mant).to(torch.uint8)
+
+    k8, v8 = draw(), draw()
+    dev = b.k_cache.device
+    poisoned_k = torch.isnan(b.k_cache.float()).cpu()
+    poisoned_v = torch.isnan(b.v_cache.float()).cpu()
+    k8[poisoned_k] = FP8_NAN_BYTE
+    v8[poisoned_v] = FP8_NAN_BYTE
+
+    def scales(std):
+        base = std / _FP8_BYTE_RMS
+        if pow2_scales:
+            base = 2.0 ** round(math.log2(base))
+            return torch.tensor([base * (2.0 ** (g % 3)) for g in range(Hkv)], dtype=torch.float32)
+        return torch.tensor([base * (1.0 + 0.25 * g / max(Hkv, 1)) for g in range(Hkv)], dtype=torch.float32)
+
+    kw = dict(b.__dict__)
+    kw.update(name=b.name + "_kv8", k_cache=k8.to(dev), v_cache=v8.to(dev), k_scale=scales(k_std).to(dev),
+              v_scale=scales(v_std).to(dev))
+    return AttnBatch(**kw)
 
 
 @dataclass

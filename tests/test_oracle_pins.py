@@ -496,3 +496,97 @@ def test_kv_write_reference_round_trip():
         assert torch.equal(got[:L - n].view(torch.int16), k_old[cu_k[i]:cu_k[i + 1]][:L - n].view(torch.int16))
     changed = (kc.view(torch.int16) != b.k_cache.view(torch.int16)).any(-1).any(1).sum()     # (block, slot) pairs
     assert int(changed) <= sum(qlens) and int((vc.view(torch.int16) != b.v_cache.view(torch.int16)).any(-1).any(1).sum()) <= sum(qlens)
+
+
+# ---- 8-bit (E4M3) key/value cache: dequantise, then the plain definition ----
+
+def test_fp8_decoding_table_matches_the_format_and_a_library():
+    """All 256 byte patterns: against the format's published constants and against torch's own
+    float8_e4m3fn decoding (a library routine the oracle does not use)."""
+    assert oracle.fp8_e4m3_value(0x38) == 1.0 and oracle.fp8_e4m3_value(0xB8) == -1.0
+    assert oracle.fp8_e4m3_value(0x7E) == 448.0           # largest finite value
+    assert oracle.fp8_e4m3_value(0x08) == 2.0 ** -6        # smallest normal
+    assert oracle.fp8_e4m3_value(0x01) == 2.0 ** -9        # smallest subnormal
+    assert oracle.fp8_e4m3_value(0x00) == 0.0 and math.copysign(1.0, oracle.fp8_e4m3_value(0x80)) == -1.0
+    assert math.isnan(oracle.fp8_e4m3_value(0x7F)) and math.isnan(oracle.fp8_e4m3_value(0xFF))
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).double()
+    for byte in range(256):
+        want, got = float(lib[byte]), oracle.fp8_e4m3_value(byte)
+        assert (math.isnan(want) and math.isnan(got)) or (want == got and math.copysign(1, want) == math.copysign(1, got)), byte
+
+
+def _dequantised(b8):
+    """fp64 K / V of an 8-bit batch through torch's decoder (not the oracle's)."""
+    Hkv = b8.num_kv_heads
+    k = b8.k_cache.view(torch.float8_e4m3fn).double() * b8.k_scale.double().view(1, Hkv, 1, 1)
+    v = b8.v_cache.view(torch.float8_e4m3fn).double() * b8.v_scale.double().view(1, Hkv, 1, 1)
+    return k, v
+
+
+def test_fp8_cache_equals_the_16_bit_path_when_bf16_holds_the_dequantised_values():
+    """Power-of-two scales: every dequantised value is a bf16 number, so running the (already pinned)
+    16-bit path on the dequantised cache must give the very same fp64 results."""
+    b = W.random_batch(801, [70, 33, 120, 16], [1, 33, 1, 5], 8, 2, 16, torch.bfloat16, num_probe_heads=4,
+                       max_sel_q=3, max_spans=3)
+    b8 = W.fp8_cache_variant(b, 802, pow2_scales=True)
+    k, v = _dequantised(b8)
+    k16, v16 = k.to(torch.bfloat16), v.to(torch.bfloat16)
+    live_k = ~torch.isnan(k)
+    assert torch.equal(k16.double()[live_k], k[live_k])          # nothing was rounded
+    kw = dict(b.__dict__); kw.update(k_cache=k16, v_cache=v16)
+    out16, mass16 = oracle.attn_probe_batch(W.AttnBatch(**kw))
+    out8, mass8 = oracle.attn_probe_batch(b8)
+    assert torch.equal(out8, out16) and torch.equal(mass8, mass16)
+    assert torch.isfinite(out8).all()
+
+
+def test_fp8_cache_matches_torch_softmax_on_dequantised_tensors():
+    """Arbitrary scales: un-paged fp64 softmax(Q K^T) V from torch on the dequantised cache."""
+    L, n, Hq, Hkv, d = 90, 90, 4, 2, 32
+    b = W.random_batch(803, [L], [n], Hq, Hkv, d, torch.bfloat16, num_probe_heads=2, max_sel_q=2, max_spans=2,
+                       shuffle=True)
+    b8 = W.fp8_cache_variant(b, 804, k_std=0.7, v_std=1.3)
+    k, v = _dequantised(b8)
+    table = b8.block_table[0].tolist()
+    K = torch.stack([k[table[j // 16], :, j % 16] for j in range(L)])     # [L, Hkv, d]
+    V = torch.stack([v[table[j // 16], :, j % 16] for j in range(L)])
+    out, mass = oracle.attn_probe_batch(b8)
+    G = Hq // Hkv
+    causal = torch.tril(torch.ones(L, L, dtype=torch.bool))
+    for h in range(Hq):
+        s = (b8.q[:, h].double() @ K[:, h // G].T) * b8.scale
+        p = torch.softmax(s.masked_fill(~causal, float("-inf")), dim=-1)
+        assert (p @ V[:, h // G] - out[:, h]).abs().max().item() < 1e-11
+    qs, ks, heads = b8.query_sel.tolist(), b8.key_spans.tolist(), b8.probe_heads.tolist()
+    for pi, h in enumerate(heads):
+        s = (b8.q[:, h].double() @ K[:, h // G].T) * b8.scale
+        p = torch.softmax(s.masked_fill(~causal, float("-inf")), dim=-1)
+        for slot in range(2):
+            t = qs[0][0] + slot
+            if not (0 <= t < qs[0][1]):
+                continue
+            for r in range(2):
+                a, e = max(ks[0][r][0], 0), min(ks[0][r][1], t + 1)
+                want = p[t, a:e].sum().item() if e > a else 0.0
+                assert abs(mass[0, pi, slot, r].item() - want) < 1e-12
+
+
+def test_fp8_cache_uniform_attention_closed_form():
+    """q = 0: every probability is 1 / (pos + 1) whatever the keys are; out is the prefix mean of the
+    dequantised values, and a key scale has no effect at all."""
+    b = W.random_batch(805, [50], [1], 4, 2, 16, torch.bfloat16, num_probe_heads=4, max_sel_q=1, max_spans=2,
+                       wild_spans=False)
+    b.q.zero_()
+    b.query_sel[0, 0], b.query_sel[0, 1] = 0, 1
+    b8 = W.fp8_cache_variant(b, 806)
+    out, mass = oracle.attn_probe_batch(b8)
+    _, v = _dequantised(b8)
+    table = b8.block_table[0].tolist()
+    V = torch.stack([v[table[j // 16], :, j % 16] for j in range(50)])
+    for h in range(4):
+        assert (out[0, h] - V[:, h // 2].mean(dim=0)).abs().max().item() < 1e-12
+    for r, (a, e) in enumerate(b8.key_spans[0].tolist()):
+        assert abs(mass[0, 0, 0, r].item() - max(0, min(e, 50) - max(a, 0)) / 50) < 1e-12
+    b8.k_scale = b8.k_scale * 3.7
+    out2, _ = oracle.attn_probe_batch(b8)
+    assert torch.equal(out, out2)
