@@ -78,6 +78,8 @@ def kv_bytes(b, decode_only: bool = True) -> float:
     lens = b.seq_lens.tolist()
     qn = b.q_lens()
     esz = 2 if str(b.dtype).endswith("bfloat16") else 4
+    if str(b.k_cache.dtype).endswith("uint8"):
+        esz = 1      # 8-bit cache
     tot = 0
     for L, n in zip(lens, qn):
         if decode_only and n != 1:
@@ -275,6 +277,19 @@ def main() -> int:
             "probe_overhead_pct": ov3["overhead_pct"],
             "workspace_mb": call3.workspace_needed / 2**20,
         }
+        # the same batch over an 8-bit (E4M3) cache: half the bytes per context token
+        b3q = W.fp8_cache_variant(b3, 960, k_std=128 ** -0.5, v_std=128 ** -0.5)
+        call3q = binding.call_from_batch(b3q, batch_kind=binding.BATCH_DECODE_ONLY)
+        t3q = time_call(call3q.launch, K, Wm)
+        k3q = kernel_times(call3q, K)
+        by3q = kv_bytes(b3q)
+        extra["decode_c3_fp8_cache"] = {
+            "workload": "c3_decode_8b with 8-bit E4M3 key/value caches (one scale per kv head)",
+            "value": by3q / (t3q["mean_ms"] * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": t3q["mean_ms"],
+            "kernels_ms": k3q, "speedup_vs_bf16_cache": t3["mean_ms"] / t3q["mean_ms"],
+            "roofline": roofline_obj("hbm", "k_decode<128,4,fp8>", by3q, k3q["decode_ms"])}
+        del b3q, call3q
+        torch.cuda.empty_cache()
         # compact q/k capture on the same batch: every key of every kv head, the probed heads' queries
         kvh = torch.arange(b3.num_kv_heads, dtype=torch.int32, device=dev)
         cu_k = torch.zeros(b3.num_seqs + 1, dtype=torch.int32, device=dev)

@@ -61,6 +61,18 @@ typedef enum {
 typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
 
 /*
+ * Element type of the key/value caches when it differs from `dtype` (a quantised cache).
+ * HOOK_KV_FP8_E4M3: one byte per element in the 8-bit E4M3 format (1 sign, 4 exponent, 3 mantissa
+ * bits, bias 7, no infinities, NaN = S.1111.111); the element a byte stands for is its value times
+ * the fp32 scale of its kv head: K[j][c] = value(k_cache byte) * k_scale[g], V alike with v_scale.
+ * Supported where it pays, on the bandwidth-bound path: batches of single-row sequences
+ * (batch_kind = HOOK_BATCH_DECODE_ONLY is then required) with HOOK_BF16 queries; the cache layout
+ * stays [num_blocks, Hkv, B, d] with one byte per element.  The paper does not discuss cache
+ * precision; this is the usual serving option of halving the bytes a decode step streams.
+ */
+typedef enum { HOOK_KV_SAME = 0, HOOK_KV_FP8_E4M3 = 1 } hook_kv_dtype;
+
+/*
  * Composition of a batch, as far as the caller knows it.  The library never reads the sequence
  * lengths on the host, so without a hint every call launches both the kernel for query chunks
  * (n_i >= 2) and the pair for single rows (n_i == 1), one of which may find nothing to do.
@@ -169,6 +181,11 @@ typedef struct hook_attn_probe_args {
   /* what the caller knows about the batch (it built cu_q_lens on the host); 0 is always valid */
   int32_t batch_kind;          /* hook_batch_kind */
   int32_t plan_mode;           /* hook_plan_mode */
+
+  /* quantised key/value cache (all zero / null: the caches hold `dtype` elements) */
+  int32_t      kv_dtype;       /* hook_kv_dtype */
+  const float* k_scale;        /* [Hkv] fp32, device: key element = stored value * k_scale[g] */
+  const float* v_scale;        /* [Hkv] fp32, device */
 } hook_attn_probe_args;
 
 /*

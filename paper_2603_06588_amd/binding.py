@@ -38,6 +38,7 @@ class HookAttnProbeArgs(ctypes.Structure):
         ("out", ctypes.c_void_p), ("mass", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p), ("batch_kind", ctypes.c_int32), ("plan_mode", ctypes.c_int32),
+        ("kv_dtype", ctypes.c_int32), ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -81,6 +82,7 @@ class HookReduceArgs(ctypes.Structure):
 
 REDUCE_SPAN_MEAN, REDUCE_RATIO_MEAN, REDUCE_RATIO_OF_SUMS = 0, 1, 2
 BATCH_MIXED, BATCH_PREFILL_ONLY, BATCH_DECODE_ONLY = 0, 1, 2
+KV_SAME, KV_FP8_E4M3 = 0, 1
 PLAN_FRESH, PLAN_REUSE = 0, 1
 (BAD_ROWS_EXCEED_CONTEXT, BAD_CONTEXT_TOO_LONG, BAD_LENGTH, BAD_BATCH_KIND, BAD_BLOCK_ID, BAD_PROBE_HEADS,
  BAD_QUERY_SEL) = 1, 2, 4, 8, 16, 32, 64
@@ -175,12 +177,13 @@ class AttnProbeCall:
 
     def __init__(self, q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
                  query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0, out=None, mass=None,
-                 workspace=None, batch_kind: int = 0, plan_mode: int = 0):
+                 workspace=None, batch_kind: int = 0, plan_mode: int = 0, k_scale=None, v_scale=None):
         lib = load_library()
         if q.dtype not in _DT:
             raise HookError(3, "hook_attn_probe (dtype)")
         dev = q.device
-        self.keep = [q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, query_sel, key_spans]
+        self.keep = [q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, query_sel, key_spans,
+                     k_scale, v_scale]
         total_q, Hq, d = q.shape
         num_blocks, Hkv, B, _ = k_cache.shape
         num_seqs, max_blocks = block_table.shape
@@ -205,6 +208,8 @@ class AttnProbeCall:
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel()
         a.batch_kind = int(batch_kind)
         a.plan_mode = int(plan_mode)
+        if k_cache.dtype == torch.uint8:      # 8-bit E4M3 bytes with one scale per kv head
+            a.kv_dtype, a.k_scale, a.v_scale = KV_FP8_E4M3, _p(k_scale), _p(v_scale)
         self.args = a
         self.workspace_needed = need
         self._fn = lib.hook_attn_probe
@@ -299,6 +304,9 @@ def hook_attn_probe_batch(b, stream=None, probe: bool = True):
 
 
 def call_from_batch(b, probe: bool = True, **kw) -> AttnProbeCall:
+    if getattr(b, "k_scale", None) is not None:
+        kw.setdefault("k_scale", b.k_scale)
+        kw.setdefault("v_scale", b.v_scale)
     return AttnProbeCall(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.cu_q_lens,
                          b.probe_heads if probe else None, b.max_sel_q, b.query_sel, b.max_spans,
                          b.key_spans, b.scale, **kw)

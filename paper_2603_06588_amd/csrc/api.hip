@@ -102,9 +102,14 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
     if (a->max_sel_q > HOOK_MAX_SEL_Q || a->max_spans > HOOK_MAX_SPANS) return HOOK_ERR_UNSUPPORTED;
     if (!a->probe_heads || !a->query_sel || !a->key_spans || !a->mass) return HOOK_ERR_NULL;
   }
+  if (a->kv_dtype != HOOK_KV_SAME && a->kv_dtype != HOOK_KV_FP8_E4M3) return HOOK_ERR_SHAPE;
+  const bool kv8 = a->kv_dtype == HOOK_KV_FP8_E4M3;
+  // the 8-bit cache is read by the single-row kernels only, with bf16 queries
+  if (kv8 && (a->dtype != HOOK_BF16 || a->batch_kind != HOOK_BATCH_DECODE_ONLY)) return HOOK_ERR_UNSUPPORTED;
   if (a->num_seqs == 0 || a->total_q == 0) return HOOK_OK;
   if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
     return HOOK_ERR_NULL;
+  if (kv8 && (!a->k_scale || !a->v_scale)) return HOOK_ERR_NULL;
   const Layout l = make_layout(a);
   // one-dimensional launch grids over the item capacities
   if (a->dtype == HOOK_BF16 &&
@@ -134,6 +139,9 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   p.key_spans = a->key_spans;
   p.out = a->out;
   p.mass = a->mass;
+  p.kv8 = kv8 ? 1 : 0;
+  p.k_scale = a->k_scale;
+  p.v_scale = a->v_scale;
   char* ws = static_cast<char*>(workspace);
   p.hdr = reinterpret_cast<PlanHeader*>(ws + l.off_hdr);
   p.pf_items = reinterpret_cast<WorkItem*>(ws + l.off_pf);

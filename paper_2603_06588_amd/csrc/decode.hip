@@ -29,7 +29,21 @@ struct DecodeCfg {
   static constexpr int PSTR = D + kPartialPad; // floats per partial record
 };
 
-template <int D, int HP>
+// 8-bit cache: two fp8 values of one 16-bit half of `w` as bf16 (exact: 3 mantissa bits)
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w, bool upper_half) {
+  bf16x2 v;
+  if (upper_half) v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
+  else v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  uint32_t u;
+  __builtin_memcpy(&u, &v, 4);
+  return u;
+}
+
+// KV8: the caches hold 8-bit E4M3 bytes ([num_blocks, Hkv, 16, D] bytes), one fp32 scale per kv head.
+// The key scale is folded into the softmax scale and the value scale into the partial output, so
+// the loop differs from the 16-bit one only in its loads and conversions: a block is half as many
+// bytes, so loads run two blocks ahead instead of one to keep as many bytes in flight.
+template <int D, int HP, bool KV8>
 __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   using C = DecodeCfg<D>;
   __shared__ float red[4][HP][C::PSTR];
@@ -62,8 +76,10 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   const __bf16* const qg = static_cast<const __bf16*>(p.q);
   const __bf16* const kg_ = static_cast<const __bf16*>(p.k_cache);
   const __bf16* const vg_ = static_cast<const __bf16*>(p.v_cache);
+  const unsigned char* const kg8 = static_cast<const unsigned char*>(p.k_cache);
+  const unsigned char* const vg8 = static_cast<const unsigned char*>(p.v_cache);
   const int* const bt = p.block_table + (size_t)seq * p.max_blocks;
-  const size_t blk_stride = (size_t)p.Hkv * kBlock * D;
+  const size_t blk_stride = (size_t)p.Hkv * kBlock * D;   // in elements (bytes for the 8-bit cache)
   const size_t head_off = (size_t)kvh * kBlock * D;
 
   // score-lane role: head j = lane % 16 (real if j < HP), key group kq = lane / 16
@@ -77,8 +93,12 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
 #pragma unroll
   for (int s = 0; s < C::KSTEPS; ++s) {
     uint4 v = make_uint4(0, 0, 0, 0);
+    // the contraction may take the dimensions in any order as long as both operands agree: with the
+    // 8-bit cache a lane's key bytes are the 16-byte piece (s / 2) of its row, so k-step s covers
+    // dimensions 64 (s / 2) + 16 kq + 8 (s % 2) + 0..7 instead of 32 s + 8 kq + 0..7
+    const int dim0 = KV8 ? 64 * (s >> 1) + 16 * kq + 8 * (s & 1) : 32 * s + 8 * kq;
     if (j < HP)
-      v = *reinterpret_cast<const uint4*>(qg + ((size_t)qrow * p.Hq + head0 + j) * D + 32 * s + 8 * kq);
+      v = *reinterpret_cast<const uint4*>(qg + ((size_t)qrow * p.Hq + head0 + j) * D + dim0);
     __builtin_memcpy(&qf[s], &v, 16);
   }
 
@@ -116,41 +136,70 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   for (int h = 0; h < HP; ++h)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
-  const float c = p.scale_log2;
+  const float c = KV8 ? p.scale_log2 * p.k_scale[kvh] : p.scale_log2;
 
-  uint4 kr[2][C::KSTEPS];
-  uint4 vr[2][C::KPL];
+  constexpr int kRing = KV8 ? 3 : 2;                       // blocks in registers
+  constexpr int kKr = KV8 ? C::KSTEPS / 2 : C::KSTEPS;     // 16-byte K pieces per lane and block
+  uint4 kr[kRing][kKr];
+  uint4 vr[kRing][C::KPL];                                 // 8-bit cache: only .x, .y are used
 
-  auto load_block = [&](int b, uint4 (&kd)[C::KSTEPS], uint4 (&vd)[C::KPL]) {
+  auto load_block = [&](int b, uint4 (&kd)[kKr], uint4 (&vd)[C::KPL]) {
     const int jb = (kstart >> 4) + b;                   // block index inside the sequence
     int blk = bt[jb];
     blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
-    const __bf16* kb = kg_ + (size_t)blk * blk_stride + head_off;
-    const __bf16* vb = vg_ + (size_t)blk * blk_stride + head_off;
     const int key_k = jb * kBlock + j;                  // this lane's key as a score-lane
     const bool ok_k = key_k < kend;
+    if constexpr (KV8) {
+      const unsigned char* kb = kg8 + (size_t)blk * blk_stride + head_off;
+      const unsigned char* vb = vg8 + (size_t)blk * blk_stride + head_off;
 #pragma unroll
-    for (int s = 0; s < C::KSTEPS; ++s) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok_k) v = load_stream16(kb + (size_t)j * D + 32 * s + 8 * kq);
-      kd[s] = v;
-    }
+      for (int h = 0; h < kKr; ++h) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ok_k) v = load_stream16(kb + (size_t)j * D + 64 * h + 16 * kq);
+        kd[h] = v;
+      }
 #pragma unroll
-    for (int i = 0; i < C::KPL; ++i) {
-      const int kl = C::KPL * vk + i;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (jb * kBlock + kl < kend) v = load_stream16(vb + (size_t)kl * D + 8 * ch);
-      vd[i] = v;
+      for (int i = 0; i < C::KPL; ++i) {
+        const int kl = C::KPL * vk + i;
+        uint2 v = make_uint2(0, 0);
+        if (jb * kBlock + kl < kend) v = *reinterpret_cast<const uint2*>(vb + (size_t)kl * D + 8 * ch);
+        vd[i] = make_uint4(v.x, v.y, 0, 0);
+      }
+    } else {
+      const __bf16* kb = kg_ + (size_t)blk * blk_stride + head_off;
+      const __bf16* vb = vg_ + (size_t)blk * blk_stride + head_off;
+#pragma unroll
+      for (int s = 0; s < C::KSTEPS; ++s) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ok_k) v = load_stream16(kb + (size_t)j * D + 32 * s + 8 * kq);
+        kd[s] = v;
+      }
+#pragma unroll
+      for (int i = 0; i < C::KPL; ++i) {
+        const int kl = C::KPL * vk + i;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (jb * kBlock + kl < kend) v = load_stream16(vb + (size_t)kl * D + 8 * ch);
+        vd[i] = v;
+      }
     }
   };
 
-  auto compute_block = [&](int b, const uint4 (&kd)[C::KSTEPS], const uint4 (&vd)[C::KPL]) {
+  auto compute_block = [&](int b, const uint4 (&kd)[kKr], const uint4 (&vd)[C::KPL]) {
     const int key0 = kstart + b * kBlock;
     f32x4 sacc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
       bf16x8 a;
-      __builtin_memcpy(&a, &kd[s], 16);
+      if constexpr (KV8) {
+        // bytes 8 (s % 2) .. 8 (s % 2) + 7 of piece s / 2
+        const uint32_t w0 = (s & 1) ? kd[s >> 1].z : kd[s >> 1].x;
+        const uint32_t w1 = (s & 1) ? kd[s >> 1].w : kd[s >> 1].y;
+        const uint4 cv = make_uint4(fp8x2_to_bf16x2(w0, false), fp8x2_to_bf16x2(w0, true),
+                                    fp8x2_to_bf16x2(w1, false), fp8x2_to_bf16x2(w1, true));
+        __builtin_memcpy(&a, &cv, 16);
+      } else {
+        __builtin_memcpy(&a, &kd[s], 16);
+      }
       sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[s], sacc, 0, 0, 0);
     }
     // lane (j, kq): sacc[r] = score of head j with key key0 + 4 kq + r
@@ -205,10 +254,17 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
 #pragma unroll
     for (int i = 0; i < C::KPL; ++i) {
       float vf[8];
-      vf[0] = bf16_lo(vd[i].x); vf[1] = bf16_hi(vd[i].x);
-      vf[2] = bf16_lo(vd[i].y); vf[3] = bf16_hi(vd[i].y);
-      vf[4] = bf16_lo(vd[i].z); vf[5] = bf16_hi(vd[i].z);
-      vf[6] = bf16_lo(vd[i].w); vf[7] = bf16_hi(vd[i].w);
+      if constexpr (KV8) {
+        const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(vd[i].x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(vd[i].x, true);
+        const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(vd[i].y, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(vd[i].y, true);
+        vf[0] = a0[0]; vf[1] = a0[1]; vf[2] = a1[0]; vf[3] = a1[1];
+        vf[4] = a2[0]; vf[5] = a2[1]; vf[6] = a3[0]; vf[7] = a3[1];
+      } else {
+        vf[0] = bf16_lo(vd[i].x); vf[1] = bf16_hi(vd[i].x);
+        vf[2] = bf16_lo(vd[i].y); vf[3] = bf16_hi(vd[i].y);
+        vf[4] = bf16_lo(vd[i].z); vf[5] = bf16_hi(vd[i].z);
+        vf[6] = bf16_lo(vd[i].w); vf[7] = bf16_hi(vd[i].w);
+      }
 #pragma unroll
       for (int h = 0; h < HP; ++h) {
         float ph;
@@ -225,14 +281,32 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
     }
   };
 
-  // stream this wave's blocks, one block of loads in flight ahead of the arithmetic
-  if (b0 < b1) load_block(b0, kr[0], vr[0]);
-  for (int b = b0; b < b1; b += 2) {
-    if (b + 1 < b1) load_block(b + 1, kr[1], vr[1]);
-    compute_block(b, kr[0], vr[0]);
-    if (b + 1 < b1) {
-      if (b + 2 < b1) load_block(b + 2, kr[0], vr[0]);
-      compute_block(b + 1, kr[1], vr[1]);
+  if constexpr (KV8) {
+    // stream this wave's blocks, two blocks of loads in flight ahead of the arithmetic
+    if (b0 < b1) load_block(b0, kr[0], vr[0]);
+    if (b0 + 1 < b1) load_block(b0 + 1, kr[1], vr[1]);
+    for (int b = b0; b < b1; b += 3) {
+      if (b + 2 < b1) load_block(b + 2, kr[2], vr[2]);
+      compute_block(b, kr[0], vr[0]);
+      if (b + 1 < b1) {
+        if (b + 3 < b1) load_block(b + 3, kr[0], vr[0]);
+        compute_block(b + 1, kr[1], vr[1]);
+      }
+      if (b + 2 < b1) {
+        if (b + 4 < b1) load_block(b + 4, kr[1], vr[1]);
+        compute_block(b + 2, kr[2], vr[2]);
+      }
+    }
+  } else {
+    // stream this wave's blocks, one block of loads in flight ahead of the arithmetic
+    if (b0 < b1) load_block(b0, kr[0], vr[0]);
+    for (int b = b0; b < b1; b += 2) {
+      if (b + 1 < b1) load_block(b + 1, kr[1], vr[1]);
+      compute_block(b, kr[0], vr[0]);
+      if (b + 1 < b1) {
+        if (b + 2 < b1) load_block(b + 2, kr[0], vr[0]);
+        compute_block(b + 1, kr[1], vr[1]);
+      }
     }
   }
 
@@ -278,7 +352,8 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   }
   __syncthreads();
 
-  // merge the 4 waves and write one partial record per head
+  // merge the 4 waves and write one partial record per head (8-bit cache: the value scale goes in here)
+  const float vscale = KV8 ? p.v_scale[kvh] : 1.0f;
   for (int idx = tid; idx < HP * C::PSTR; idx += 256) {
     const int h = idx / C::PSTR, col = idx % C::PSTR;
     float mm = fmaxf(fmaxf(red[0][h][D], red[1][h][D]), fmaxf(red[2][h][D], red[3][h][D]));
@@ -293,6 +368,7 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
         const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - mm);
         out += e * red[ww][h][col];
       }
+      if (KV8 && col < D) out *= vscale;
     } else {
       out = 0.0f;
     }
@@ -392,7 +468,8 @@ hipError_t launch_decode_dh(const AttnParams& p, hipStream_t st) {
   const long long grid = (long long)p.dec_cap * p.Hkv * p.dec_hgroups;
   if (grid <= 0) return hipSuccess;
   if (!grid_fits(grid)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_decode<D, HP>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  if (p.kv8) hipLaunchKernelGGL((k_decode<D, HP, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((k_decode<D, HP, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

@@ -66,6 +66,10 @@ struct AttnParams {
   const int* key_spans;
   void* out;
   float* mass;
+  // 8-bit (E4M3) key/value cache: bytes instead of `dtype` elements, one fp32 scale per kv head
+  int kv8;
+  const float* k_scale;
+  const float* v_scale;
   // workspace carve-up
   PlanHeader* hdr;
   WorkItem* pf_items;

@@ -468,6 +468,7 @@ __global__ __launch_bounds__(256) void k_zero_mass(float* ptr, size_t n) {
 extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   using namespace hook;
   if (!a) return HOOK_ERR_NULL;
+  if (a->kv_dtype != HOOK_KV_SAME) return HOOK_ERR_UNSUPPORTED;   // reads 16-bit keys only
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
     return HOOK_ERR_SHAPE;
