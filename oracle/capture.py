@@ -38,12 +38,53 @@ def capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_se
     return q_out, k_out, torch.tensor(cu_k, dtype=torch.int32)
 
 
-def kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache):
+def _e4m3_table():
+    """The 127 non-negative finite numbers of the 8-bit E4M3 format, by byte value 0x00 .. 0x7E,
+    written out from the format's definition (bias 7, 3 mantissa bits, subnormals for E = 0)."""
+    vals = []
+    for byte in range(0x7F):
+        E, M = byte >> 3, byte & 7
+        vals.append((M / 8.0) * 2.0 ** -6 if E == 0 else (1.0 + M / 8.0) * 2.0 ** (E - 7))
+    return vals
+
+
+def quantize_e4m3(x: torch.Tensor, scale: float) -> torch.Tensor:
+    """Bytes of an 8-bit E4M3 cache for the fp32 / bf16 values `x` under one scale:
+    y = x / scale as a correctly rounded fp32 quotient, clamped to [-448, 448] (the format has no
+    infinities: out-of-range values saturate), then the NEAREST representable number, ties to the
+    one whose last mantissa bit is 0; the sign bit is kept (so -0 and negative underflow give 0x80),
+    NaN gives the NaN byte 0x7F.  Written as a search of the 127-entry table: the definition of
+    round-to-nearest-even, not a bit trick."""
+    table = _e4m3_table()
+    # the fp64 quotient of two fp32 numbers rounded to fp32 is the correctly rounded fp32 quotient
+    y = (x.double() / float(torch.tensor(scale, dtype=torch.float32))).float().double().flatten().tolist()
+    out = []
+    for v in y:
+        if v != v:
+            out.append(0x7F)
+            continue
+        neg = (v < 0) or (v == 0 and str(v).startswith("-"))
+        a = min(abs(v), 448.0)
+        best = 0
+        for byte in range(1, 0x7F):
+            d_new, d_best = abs(table[byte] - a), abs(table[best] - a)
+            if d_new < d_best or (d_new == d_best and (byte & 1) == 0):
+                best = byte
+        out.append(best | (0x80 if neg else 0))
+    return torch.tensor(out, dtype=torch.uint8).reshape(x.shape)
+
+
+def kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache, k_scale=None, v_scale=None):
     """Reference for writing the new tokens' K/V into the paged cache (the attention call expects
     them there): returns updated copies of (k_cache, v_cache).  Row t of sequence i goes to position
-    L_i - n_i + t; plain loops, single-row copies."""
+    L_i - n_i + t; plain loops, single-row copies.  With uint8 caches (8-bit E4M3) and per-kv-head
+    scales the rows are quantised on the way (quantize_e4m3)."""
     k_cache, v_cache = k_cache.cpu().clone(), v_cache.cpu().clone()
     k_new, v_new = k_new.cpu(), v_new.cpu()
+    if k_cache.dtype == torch.uint8:
+        ks, vs = k_scale.cpu().tolist(), v_scale.cpu().tolist()
+        k_new = torch.stack([quantize_e4m3(k_new[:, g].float(), ks[g]) for g in range(k_new.shape[1])], dim=1)
+        v_new = torch.stack([quantize_e4m3(v_new[:, g].float(), vs[g]) for g in range(v_new.shape[1])], dim=1)
     table = block_table.cpu().tolist()
     lens = seq_lens.cpu().tolist()
     cu = cu_q_lens.cpu().tolist()

@@ -590,3 +590,55 @@ def test_fp8_cache_uniform_attention_closed_form():
     b8.k_scale = b8.k_scale * 3.7
     out2, _ = oracle.attn_probe_batch(b8)
     assert torch.equal(out, out2)
+
+
+def test_fp8_quantiser_is_round_to_nearest_even_with_saturation():
+    """oracle.capture.quantize_e4m3: every finite number of the format maps to its own byte, torch's
+    own float8_e4m3fn conversion (a library routine) agrees wherever it is defined (|y| <= 448),
+    midpoints go to the even neighbour, values beyond the range saturate, signs of zero survive."""
+    from oracle.capture import quantize_e4m3
+    finite = torch.tensor([b for b in range(256) if (b & 0x7F) != 0x7F], dtype=torch.uint8)
+    assert torch.equal(quantize_e4m3(finite.view(torch.float8_e4m3fn).float(), 1.0), finite)
+    gen = torch.Generator().manual_seed(11)
+    x = torch.cat([torch.randn(3000, generator=gen) * 4, torch.randn(2000, generator=gen) * 0.01,
+                   (torch.rand(500, generator=gen) - 0.5) * 890])
+    assert torch.equal(quantize_e4m3(x, 1.0), x.to(torch.float8_e4m3fn).view(torch.uint8))
+    # a scale: the bytes of x under scale s are the bytes of fl32(x / s) under scale 1
+    s = 0.37
+    assert torch.equal(quantize_e4m3(x, s), quantize_e4m3((x.double() / float(torch.tensor(s))).float(), 1.0))
+    cases = [(1.0625, 0x38), (1.1875, 0x3A), (2.0 ** -10, 0x00), (3 * 2.0 ** -10, 0x02), (449.0, 0x7E), (1e30, 0x7E),
+             (-1e30, 0xFE), (464.0, 0x7E), (-0.0, 0x80), (-2.0 ** -12, 0x80), (0.0, 0x00), (432.0, 0x7E), (400.0, 0x7C)]
+    for v, want in cases:
+        assert int(quantize_e4m3(torch.tensor([v]), 1.0)[0]) == want, v
+    assert int(quantize_e4m3(torch.tensor([float("nan")]), 1.0)[0]) == 0x7F
+
+
+def test_fp8_kv_write_places_quantised_rows():
+    """kv_write into an 8-bit cache: positions as for the 16-bit cache, bytes from the quantiser; rows
+    holding numbers the format has (times the head's scale) read back exactly."""
+    from oracle.capture import kv_write, quantize_e4m3
+    b = W.random_batch(811, [40, 9, 33], [7, 9, 1], 4, 2, 16, torch.bfloat16, num_probe_heads=1)
+    b8 = W.fp8_cache_variant(b, 812, pow2_scales=True)
+    gen = torch.Generator().manual_seed(813)
+    k_new = (torch.randn((b.total_q, 2, 16), generator=gen) * 2).to(torch.bfloat16)
+    v_new = (torch.randn((b.total_q, 2, 16), generator=gen) * 2).to(torch.bfloat16)
+    # row 3: numbers the format holds, times the scale
+    exact = torch.tensor([0x38, 0x41, 0xC5, 0x10, 0x01, 0x7E, 0x80, 0x2A] * 2, dtype=torch.uint8)
+    for g in range(2):
+        k_new[3, g] = (exact.view(torch.float8_e4m3fn).double() * float(b8.k_scale[g])).to(torch.bfloat16)
+    k2, v2 = kv_write(k_new, v_new, b8.block_table, b8.seq_lens, b8.cu_q_lens, b8.k_cache, b8.v_cache, b8.k_scale,
+                      b8.v_scale)
+    cu, lens, table = b8.cu_q_lens.tolist(), b8.seq_lens.tolist(), b8.block_table.tolist()
+    touched = torch.zeros_like(b8.k_cache, dtype=torch.bool)
+    for i in range(3):
+        n = cu[i + 1] - cu[i]
+        for t in range(n):
+            pos = lens[i] - n + t
+            blk = table[i][pos // 16]
+            for g in range(2):
+                assert torch.equal(k2[blk, g, pos % 16], quantize_e4m3(k_new[cu[i] + t, g].float(), float(b8.k_scale[g])))
+                assert torch.equal(v2[blk, g, pos % 16], quantize_e4m3(v_new[cu[i] + t, g].float(), float(b8.v_scale[g])))
+            touched[blk, :, pos % 16] = True
+    assert torch.equal(k2[~touched], b8.k_cache[~touched]) and torch.equal(v2[~touched], b8.v_cache[~touched])
+    blk, slot = table[0][(lens[0] - 7 + 3) // 16], (lens[0] - 7 + 3) % 16
+    assert torch.equal(k2[blk, 0, slot], exact) and torch.equal(k2[blk, 1, slot], exact)
