@@ -422,6 +422,15 @@ def main() -> int:
         kw_bytes = 4.0 * k_new.numel() * k_new.element_size()       # K and V rows read once, written once
         extra["mixed_c5"]["kv_write"] = {"ms": tkw["mean_ms"],
                                          "roofline": roofline_obj("hbm", "k_kv_write", kw_bytes, tkw["mean_ms"])}
+        # the same write done by the attention call itself (spare workgroups of its planning launch)
+        call5w = binding.call_from_batch(b5, k_new=k_new, v_new=v_new)
+        t5w = time_batch(call5w.launch, K, Wm)
+        t5sep = time_batch(lambda: (binding.hook_kv_write(k_new, v_new, b5.block_table, b5.seq_lens, b5.cu_q_lens,
+                                                          b5.k_cache, b5.v_cache), call5.launch()), K, Wm)
+        extra["mixed_c5"]["kv_write"]["attn_call_back_to_back_ms"] = time_batch(call5.launch, K, Wm)
+        extra["mixed_c5"]["kv_write"]["attn_call_writing_kv_ms"] = t5w
+        extra["mixed_c5"]["kv_write"]["kv_write_then_attn_call_ms"] = t5sep
+        del call5w
         del k_new, v_new
         t5f = {"mean_ms": time_batch(fused_step, K, Wm)}
         t5u = {"mean_ms": time_batch(unfused_step, K, Wm)}

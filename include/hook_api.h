@@ -186,6 +186,13 @@ typedef struct hook_attn_probe_args {
   int32_t      kv_dtype;       /* hook_kv_dtype */
   const float* k_scale;        /* [Hkv] fp32, device: key element = stored value * k_scale[g] */
   const float* v_scale;        /* [Hkv] fp32, device */
+
+  /* optional: the new tokens' keys and values, [total_q, Hkv, d] of `dtype`, device.  When both are
+     given the call first writes them into k_cache / v_cache at positions L_i - n_i + t (exactly what
+     hook_kv_write does, quantising for an 8-bit cache), inside its first launch, and only then reads
+     the caches: the one place where the call writes through k_cache / v_cache. */
+  const void*  k_new;
+  const void*  v_new;
 } hook_attn_probe_args;
 
 /*
@@ -346,7 +353,11 @@ hook_status hook_capture_qk(const hook_capture_qk_args* args);
  * Sequences with n_i > L_i, negative lengths or rows outside [0, total_q) are skipped; a block id
  * outside [0, num_blocks) or a position beyond max_blocks_per_seq * B drops that token's write
  * (nothing outside the cache is ever written).  Two sequences must not own the same block.
- *   k_new, v_new   [total_q, Hkv, d], dtype of the cache, device
+ *   k_new, v_new   [total_q, Hkv, d], dtype `dtype`, device
+ * With kv_dtype = HOOK_KV_FP8_E4M3 the rows (bf16) are quantised on the way: stored byte = the E4M3
+ * number nearest to fl32(x / scale[g]) clamped to [-448, 448] (the format has no infinities), ties to
+ * the even mantissa, sign kept, NaN -> NaN; the inverse of the dequantisation hook_attn_probe applies.
+ * hook_attn_probe can do this write itself (its k_new / v_new fields) and save the launch.
  */
 typedef struct hook_kv_write_args {
   int32_t num_seqs, total_q, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks;
@@ -359,6 +370,10 @@ typedef struct hook_kv_write_args {
   void*          k_cache;
   void*          v_cache;
   void*          stream;
+  /* quantising write into an 8-bit cache (all zero / null: the cache holds `dtype` elements) */
+  int32_t        kv_dtype;     /* hook_kv_dtype; HOOK_KV_FP8_E4M3 needs dtype = HOOK_BF16 */
+  const float*   k_scale;      /* [Hkv] fp32, device */
+  const float*   v_scale;      /* [Hkv] fp32, device */
 } hook_kv_write_args;
 
 hook_status hook_kv_write(const hook_kv_write_args* args);

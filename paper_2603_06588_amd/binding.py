@@ -39,6 +39,7 @@ class HookAttnProbeArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p), ("batch_kind", ctypes.c_int32), ("plan_mode", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+        ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
     ]
 
 
@@ -65,6 +66,7 @@ class HookKvWriteArgs(ctypes.Structure):
         ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
         ("seq_lens", ctypes.c_void_p), ("cu_q_lens", ctypes.c_void_p),
         ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p), ("stream", ctypes.c_void_p),
+        ("kv_dtype", ctypes.c_int32), ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -177,13 +179,14 @@ class AttnProbeCall:
 
     def __init__(self, q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads=None, max_sel_q=1,
                  query_sel=None, max_spans=1, key_spans=None, scale: float = 0.0, out=None, mass=None,
-                 workspace=None, batch_kind: int = 0, plan_mode: int = 0, k_scale=None, v_scale=None):
+                 workspace=None, batch_kind: int = 0, plan_mode: int = 0, k_scale=None, v_scale=None,
+                 k_new=None, v_new=None):
         lib = load_library()
         if q.dtype not in _DT:
             raise HookError(3, "hook_attn_probe (dtype)")
         dev = q.device
         self.keep = [q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe_heads, query_sel, key_spans,
-                     k_scale, v_scale]
+                     k_scale, v_scale, k_new, v_new]
         total_q, Hq, d = q.shape
         num_blocks, Hkv, B, _ = k_cache.shape
         num_seqs, max_blocks = block_table.shape
@@ -210,6 +213,7 @@ class AttnProbeCall:
         a.plan_mode = int(plan_mode)
         if k_cache.dtype == torch.uint8:      # 8-bit E4M3 bytes with one scale per kv head
             a.kv_dtype, a.k_scale, a.v_scale = KV_FP8_E4M3, _p(k_scale), _p(v_scale)
+        a.k_new, a.v_new = _p(k_new), _p(v_new)
         self.args = a
         self.workspace_needed = need
         self._fn = lib.hook_attn_probe
@@ -323,8 +327,10 @@ def hook_residual_add_steer(hidden, delta, vec, alpha: float, token_mask=None, s
     return hidden
 
 
-def hook_kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache, stream=None) -> None:
-    """Scatter the new tokens' K/V rows ([total_q, Hkv, d]) into the paged cache, in place."""
+def hook_kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cache, stream=None, k_scale=None,
+                  v_scale=None) -> None:
+    """Scatter the new tokens' K/V rows ([total_q, Hkv, d]) into the paged cache, in place (quantising
+    when the cache is uint8 E4M3 bytes with per-kv-head scales)."""
     lib = load_library()
     total_q, Hkv, d = k_new.shape
     num_blocks, _, B, _ = k_cache.shape
@@ -335,6 +341,8 @@ def hook_kv_write(k_new, v_new, block_table, seq_lens, cu_q_lens, k_cache, v_cac
     a.k_new, a.v_new, a.block_table = _p(k_new), _p(v_new), _p(block_table)
     a.seq_lens, a.cu_q_lens = _p(seq_lens), _p(cu_q_lens)
     a.k_cache, a.v_cache, a.stream = _p(k_cache), _p(v_cache), _stream_handle(stream)
+    if k_cache.dtype == torch.uint8:
+        a.kv_dtype, a.k_scale, a.v_scale = KV_FP8_E4M3, _p(k_scale), _p(v_scale)
     st = lib.hook_kv_write(ctypes.byref(a))
     if st != HOOK_OK:
         raise HookError(st, "hook_kv_write")

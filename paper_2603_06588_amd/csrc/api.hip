@@ -110,6 +110,7 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
     return HOOK_ERR_NULL;
   if (kv8 && (!a->k_scale || !a->v_scale)) return HOOK_ERR_NULL;
+  if ((a->k_new == nullptr) != (a->v_new == nullptr)) return HOOK_ERR_NULL;
   const Layout l = make_layout(a);
   // one-dimensional launch grids over the item capacities
   if (a->dtype == HOOK_BF16 &&
@@ -142,6 +143,17 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   p.kv8 = kv8 ? 1 : 0;
   p.k_scale = a->k_scale;
   p.v_scale = a->v_scale;
+  const bool writes_kv = a->k_new != nullptr;
+  if (writes_kv) {
+    const int esize = a->dtype == HOOK_BF16 ? 2 : 4;
+    KvWriteParams& w = p.kvw;
+    w.num_seqs = a->num_seqs; w.total_q = a->total_q; w.Hkv = a->num_kv_heads; w.max_blocks = a->max_blocks_per_seq;
+    w.num_blocks = a->num_blocks; w.row_chunks = a->head_dim * esize / 16; w.kv8 = p.kv8;
+    w.k_new = static_cast<const uint4*>(a->k_new); w.v_new = static_cast<const uint4*>(a->v_new);
+    w.block_table = a->block_table; w.seq_lens = a->seq_lens; w.cu_q_lens = a->cu_q_lens;
+    w.k_cache = const_cast<void*>(a->k_cache); w.v_cache = const_cast<void*>(a->v_cache);
+    w.k_scale = a->k_scale; w.v_scale = a->v_scale;
+  }
   char* ws = static_cast<char*>(workspace);
   p.hdr = reinterpret_cast<PlanHeader*>(ws + l.off_hdr);
   p.pf_items = reinterpret_cast<WorkItem*>(ws + l.off_pf);
@@ -157,6 +169,10 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   hipStream_t st = static_cast<hipStream_t>(a->stream);
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
   if (!mark(0)) return HOOK_ERR_LAUNCH;
+  // the planning launch carries the cache write; where there is no such launch it gets its own
+  if (writes_kv && (a->dtype == HOOK_F32 || a->plan_mode == HOOK_PLAN_REUSE) &&
+      launch_kv_write(p.kvw, st) != hipSuccess)
+    return HOOK_ERR_LAUNCH;
   if (a->dtype == HOOK_F32) {
     if (launch_attn_f32(p, a->head_dim, st) != hipSuccess) return HOOK_ERR_LAUNCH;
     for (int i = 1; i < 5; ++i)

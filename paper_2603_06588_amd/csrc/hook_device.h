@@ -49,6 +49,22 @@ struct PlanHeader {
 // decode: one record {seq, chunk index, L, global q row}.
 typedef int4 WorkItem;
 
+// Cache write of the new tokens' rows (kv_write_device.h)
+struct KvWriteParams {
+  int num_seqs, total_q, Hkv, max_blocks, num_blocks;
+  int row_chunks;   // 16-byte chunks per (token, kv head) row of k_new / v_new
+  int kv8;          // the cache holds 8-bit E4M3 bytes: rows (bf16) are quantised on the way
+  const uint4* k_new;
+  const uint4* v_new;
+  const int* block_table;
+  const int* seq_lens;
+  const int* cu_q_lens;
+  void* k_cache;
+  void* v_cache;
+  const float* k_scale;   // [Hkv], kv8 only
+  const float* v_scale;
+};
+
 struct AttnParams {
   int num_seqs, total_q, Hq, Hkv, G, max_blocks, num_blocks;
   float scale_log2;                 // softmax scale * log2(e)
@@ -66,6 +82,8 @@ struct AttnParams {
   const int* key_spans;
   void* out;
   float* mass;
+  // new tokens' key/value rows to be written into the cache before anything reads it (kvw.k_new != null)
+  KvWriteParams kvw;
   // 8-bit (E4M3) key/value cache: bytes instead of `dtype` elements, one fp32 scale per kv head
   int kv8;
   const float* k_scale;
@@ -162,6 +180,7 @@ inline hipError_t raise_lds_limit_once(const void* kernel, int bytes, std::atomi
 inline bool grid_fits(long long workgroups) { return workgroups >= 0 && workgroups <= 0x7fffffffLL; }
 
 hipError_t launch_plan(const AttnParams& p, hipStream_t st);
+hipError_t launch_kv_write(const KvWriteParams& p, hipStream_t st);
 hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st);
 hipError_t launch_prefill128(const AttnParams& p, hipStream_t st);
 hipError_t launch_decode(const AttnParams& p, int D, hipStream_t st);

@@ -8,7 +8,7 @@
 //                  (256..8192) is the largest that still gives the decode grid enough workgroups
 //                  to fill the chip; they are processed longest first.
 // The same launch zero-fills `mass`.
-#include "hook_device.h"
+#include "kv_write_device.h"
 
 namespace hook {
 
@@ -47,7 +47,21 @@ __global__ __launch_bounds__(kPlanThreads) void k_plan(const AttnParams p) {
   const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
   for (size_t i = (size_t)blockIdx.x * kPlanThreads + tid; i < nmass; i += (size_t)gridDim.x * kPlanThreads)
     p.mass[i] = 0.0f;
-  if (blockIdx.x != 0) return;
+  if (blockIdx.x != 0) {
+    // the spare blocks also write the new tokens' key/value rows into the cache, if the call brings
+    // them: the attention kernels are launched after this one, so they find the cache complete
+    // (a block works on four tiles of rows at a time, one per group of 256 threads; the trip count
+    // is the same for every group because the tile code synchronises the whole block)
+    if (p.kvw.k_new != nullptr) {
+      constexpr int kGroups = kPlanThreads / 256;
+      __shared__ long long dst_row[kGroups][kKvRowTile];
+      const int ntiles = (p.kvw.total_q + kKvRowTile - 1) / kKvRowTile;
+      const int group = tid >> 8;
+      for (int t0 = (blockIdx.x - 1) * kGroups; t0 < ntiles; t0 += (gridDim.x - 1) * kGroups)
+        kv_write_tile<256>(p.kvw, t0 + group, tid & 255, dst_row[group]);
+    }
+    return;
+  }
 
   __shared__ int hist[kPlanBuckets];
   __shared__ int sh_cnt[kChunkSizes];   // number of decode chunks for each candidate size
@@ -311,6 +325,12 @@ hipError_t launch_plan(const AttnParams& p, hipStream_t st) {
   const size_t nmass = (size_t)p.num_seqs * p.P * p.NQ * p.S;
   int blocks = 1 + (int)((nmass + 8 * kPlanThreads - 1) / (8 * kPlanThreads));
   if (blocks > 64) blocks = 64;
+  if (p.kvw.k_new != nullptr) {   // one spare block per four tiles of rows to write, up to two per CU
+    const int tiles = (p.kvw.total_q + kKvRowTile - 1) / kKvRowTile;
+    const int groups = (tiles + kPlanThreads / 256 - 1) / (kPlanThreads / 256);
+    const int want = 1 + (groups < 512 ? groups : 512);
+    if (want > blocks) blocks = want;
+  }
   hipLaunchKernelGGL(k_plan, dim3(blocks), dim3(kPlanThreads), 0, st, p);
   return hipGetLastError();
 }

@@ -109,3 +109,99 @@ def test_kv_write_then_attention_and_invalid_contents():
     binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bad_lens, bd.cu_q_lens, bd.k_cache, bd.v_cache)
     torch.cuda.synchronize()
     assert torch.equal(bits(bd.k_cache), bits(before_k))
+
+
+# ---- quantising write into an 8-bit (E4M3) cache ----
+
+def test_kv_write_quantises_into_fp8_cache_like_the_reference():
+    """Bytes written by the library equal the oracle's search-the-table quantiser, on random rows and on
+    rows built from midpoints of the format, saturating, tiny, signed-zero and NaN values."""
+    from oracle.capture import kv_write
+    from paper_2603_06588_amd import binding
+    b = W.random_batch(320, [333, 17, 64, 1000, 9], [100, 1, 64, 1, 0], 8, 2, 128, torch.bfloat16, num_probe_heads=1,
+                       max_sel_q=1, poison=False)
+    b8 = W.fp8_cache_variant(b, 321, k_std=1.0, v_std=0.3)
+    gen = torch.Generator().manual_seed(322)
+    k_new = (torch.randn((b.total_q, 2, 128), generator=gen) * 1.5).to(torch.bfloat16)
+    v_new = (torch.randn((b.total_q, 2, 128), generator=gen) * 0.4).to(torch.bfloat16)
+    ks, vs = b8.k_scale.tolist(), b8.v_scale.tolist()
+    # row 5: every number of the format and the midpoints between neighbours, times the head's scale
+    vals = torch.arange(0x7F, dtype=torch.uint8).view(torch.float8_e4m3fn).double()
+    mids = (vals[:-1] + vals[1:]) / 2
+    special = torch.cat([mids[:120], torch.tensor([500.0, 1e6, -1e6, 2.0 ** -10, 2.0 ** -11, -2.0 ** -11, -0.0, 0.0])])
+    for g in range(2):
+        k_new[5, g] = (special * ks[g]).to(torch.bfloat16)
+        v_new[5, g] = (-special * vs[g]).to(torch.bfloat16)
+    k_new[6, 0, :4] = torch.tensor([float("nan"), float("inf"), float("-inf"), 0.0]).to(torch.bfloat16)
+    want_k, want_v = kv_write(k_new, v_new, b8.block_table, b8.seq_lens, b8.cu_q_lens, b8.k_cache, b8.v_cache,
+                              b8.k_scale, b8.v_scale)
+    bd = b8.to(DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bd.seq_lens, bd.cu_q_lens, bd.k_cache,
+                          bd.v_cache, k_scale=bd.k_scale, v_scale=bd.v_scale)
+    torch.cuda.synchronize()
+    got_k, got_v = bd.k_cache.cpu(), bd.v_cache.cpu()
+    for got, want in ((got_k, want_k), (got_v, want_v)):
+        nan_w, nan_g = (want & 0x7F) == 0x7F, (got & 0x7F) == 0x7F
+        assert torch.equal(nan_w, nan_g)
+        diff = (got != want) & ~nan_w
+        assert int(diff.sum()) == 0, (got[diff][:8], want[diff][:8])
+
+
+@pytest.mark.parametrize("variant", ["bf16_mixed", "bf16_plan_reuse", "f32", "fp8_decode"])
+def test_attention_call_writes_the_new_rows_itself(variant):
+    """k_new / v_new given to hook_attn_probe: the cache ends up as hook_kv_write leaves it and the results
+    are those of a call on the written cache, bit for bit; before the call the new tokens' slots hold NaN."""
+    from paper_2603_06588_amd import binding
+    f32 = variant == "f32"
+    dtype, d = (torch.float32, 64) if f32 else (torch.bfloat16, 128)
+    if variant == "fp8_decode":
+        lens, qlens = [500, 33, 257, 1025], [1, 1, 1, 1]
+    elif f32:
+        lens, qlens = [90, 40, 33], [30, 1, 33]
+    else:
+        lens, qlens = [300, 150, 700, 64], [300, 1, 20, 64]
+    b = W.random_batch(330, lens, qlens, 8, 2, d, dtype, std=1.0, num_probe_heads=2, max_sel_q=2, max_spans=2)
+    if variant == "fp8_decode":
+        b.query_sel[:, 0], b.query_sel[:, 1] = 0, 1
+        b = W.fp8_cache_variant(b, 331)
+    gen = torch.Generator().manual_seed(332)
+    k_new = torch.randn((b.total_q, 2, d), generator=gen).to(dtype)
+    v_new = torch.randn((b.total_q, 2, d), generator=gen).to(dtype)
+    # the slots of the new tokens start out as NaN (NaN bytes in the 8-bit cache)
+    cu, L, table = b.cu_q_lens.tolist(), b.seq_lens.tolist(), b.block_table.tolist()
+    for i in range(b.num_seqs):
+        for t in range(cu[i + 1] - cu[i]):
+            pos = L[i] - (cu[i + 1] - cu[i]) + t
+            if b.k_cache.dtype == torch.uint8:
+                b.k_cache[table[i][pos // 16], :, pos % 16] = 0x7F
+                b.v_cache[table[i][pos // 16], :, pos % 16] = 0x7F
+            else:
+                b.k_cache[table[i][pos // 16], :, pos % 16] = float("nan")
+                b.v_cache[table[i][pos // 16], :, pos % 16] = float("nan")
+    kind = binding.BATCH_DECODE_ONLY if variant == "fp8_decode" else binding.BATCH_MIXED
+    # reference: separate write, then the call
+    ref = b.to(DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), ref.block_table, ref.seq_lens, ref.cu_q_lens, ref.k_cache,
+                          ref.v_cache, k_scale=ref.k_scale, v_scale=ref.v_scale)
+    ref_call = binding.call_from_batch(ref, batch_kind=kind)
+    ref_call.launch()
+    torch.cuda.synchronize()
+    assert torch.isfinite(ref_call.out.float()).all()
+    # the call that writes by itself
+    one = b.to(DEV)
+    kn, vn = k_new.to(DEV), v_new.to(DEV)
+    if variant == "bf16_plan_reuse":
+        call = binding.call_from_batch(one, batch_kind=kind, workspace=ref_call.workspace, plan_mode=binding.PLAN_REUSE,
+                                       k_new=kn, v_new=vn, mass=torch.zeros_like(ref_call.mass))
+    else:
+        call = binding.call_from_batch(one, batch_kind=kind, k_new=kn, v_new=vn)
+    call.launch()
+    torch.cuda.synchronize()
+    assert torch.equal(bits(call.out), bits(ref_call.out))
+    assert torch.equal(bits(call.mass), bits(ref_call.mass))
+    if one.k_cache.dtype == torch.uint8:
+        assert torch.equal(one.k_cache, ref.k_cache) and torch.equal(one.v_cache, ref.v_cache)
+    else:
+        live = ~torch.isnan(ref.k_cache.float())
+        assert torch.equal(bits(one.k_cache)[live.cpu()], bits(ref.k_cache)[live.cpu()])
+        assert torch.equal(torch.isnan(one.k_cache.float()), ~live)
