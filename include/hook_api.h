@@ -79,6 +79,11 @@ typedef enum { HOOK_KV_SAME = 0, HOOK_KV_FP8_E4M3 = 1 } hook_kv_dtype;
  * With a hint the launches that cannot have work are left out (two of four for a prefill-only
  * batch).  A sequence that contradicts the hint is NOT computed: its rows of `out` stay untouched,
  * its `mass` entries are zero and bit 3 of the device status word is set.
+ * A small HOOK_BATCH_DECODE_ONLY batch (HOOK_BF16, at most 512 (sequence, kv head, head group)
+ * triples, i.e. up to 64 sequences at 8 kv heads) plans itself: every sequence is cut into the same
+ * number of parts, the workgroups read the lengths themselves and the planning launch is left out
+ * (two launches instead of three).  Results are the same to rounding order; the status word is
+ * written as always.
  */
 typedef enum hook_batch_kind {
   HOOK_BATCH_MIXED = 0,         /* anything (default) */

@@ -11,6 +11,10 @@ namespace {
 using namespace hook;
 
 constexpr size_t kAlign = 256;
+// A batch of single rows with at most this many (sequence, kv head, head group) triples plans
+// itself: every sequence is cut into the same number of parts and the planning launch, a quarter
+// of such a call, is left out.  Larger batches keep the planner, which balances ragged lengths.
+constexpr long long kSelfPlanMaxTriples = 512;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
@@ -68,6 +72,18 @@ Layout make_layout(const hook_attn_probe_args* a) {
   off = align_up(off + sizeof(float) * (size_t)l.dec_cap * a->num_q_heads * (a->head_dim + kPartialPad));
   l.total = off;
   return l;
+}
+
+// Parts per sequence of a self-planned batch of single rows, 0 where the planner is kept.  Enough
+// parts to fill the chip; the records of part j of sequence i sit in slot i * parts + j, so the
+// slot capacity of the workspace bounds the count as well.
+int self_plan_parts(const hook_attn_probe_args* a, const Layout& l) {
+  if (a->dtype != HOOK_BF16 || a->batch_kind != HOOK_BATCH_DECODE_ONLY || a->num_seqs <= 0) return 0;
+  const long long triples = (long long)a->num_seqs * a->num_kv_heads * l.dec_hgroups;
+  if (triples > kSelfPlanMaxTriples) return 0;
+  long long parts = (kDecodeFillWgs + triples - 1) / triples;
+  if (parts > l.dec_cap / a->num_seqs) parts = l.dec_cap / a->num_seqs;
+  return (int)parts;
 }
 
 }  // namespace
@@ -165,12 +181,14 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   p.hpw = l.hpw; p.rows_per_wg = l.rows_per_wg; p.hgroups = l.hgroups;
   p.dec_hp = l.dec_hp; p.dec_hgroups = l.dec_hgroups;
   p.batch_kind = a->batch_kind;
+  p.dec_parts = self_plan_parts(a, l);
+  p.plan_fresh = a->plan_mode == HOOK_PLAN_FRESH;
 
   hipStream_t st = static_cast<hipStream_t>(a->stream);
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
   if (!mark(0)) return HOOK_ERR_LAUNCH;
   // the planning launch carries the cache write; where there is no such launch it gets its own
-  if (writes_kv && (a->dtype == HOOK_F32 || a->plan_mode == HOOK_PLAN_REUSE) &&
+  if (writes_kv && (a->dtype == HOOK_F32 || a->plan_mode == HOOK_PLAN_REUSE || p.dec_parts > 0) &&
       launch_kv_write(p.kvw, st) != hipSuccess)
     return HOOK_ERR_LAUNCH;
   if (a->dtype == HOOK_F32) {
@@ -179,8 +197,10 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
       if (!mark(i)) return HOOK_ERR_LAUNCH;
     return HOOK_OK;
   }
-  // a reusing call finds the work lists of the same batch in the workspace
-  if ((a->plan_mode == HOOK_PLAN_FRESH && launch_plan(p, st) != hipSuccess) || !mark(1)) return HOOK_ERR_LAUNCH;
+  // a reusing call finds the work lists of the same batch in the workspace; a self-planned batch
+  // of single rows needs none
+  if ((a->plan_mode == HOOK_PLAN_FRESH && p.dec_parts == 0 && launch_plan(p, st) != hipSuccess) || !mark(1))
+    return HOOK_ERR_LAUNCH;
   const bool chunks = a->batch_kind != HOOK_BATCH_DECODE_ONLY, singles = a->batch_kind != HOOK_BATCH_PREFILL_ONLY;
   if ((chunks && launch_prefill(p, a->head_dim, st) != hipSuccess) || !mark(2)) return HOOK_ERR_LAUNCH;
   if ((singles && launch_decode(p, a->head_dim, st) != hipSuccess) || !mark(3)) return HOOK_ERR_LAUNCH;

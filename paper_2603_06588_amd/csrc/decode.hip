@@ -43,35 +43,17 @@ __device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w, bool upper_half)
 // The key scale is folded into the softmax scale and the value scale into the partial output, so
 // the loop differs from the 16-bit one only in its loads and conversions: a block is half as many
 // bytes, so loads run two blocks ahead instead of one to keep as many bytes in flight.
+// The keys [kstart, kend) of one sequence for one (kv head, head group): four waves split the cache
+// blocks, merge in LDS and leave one partial record per head in slot `item`.
 template <int D, int HP, bool KV8>
-__global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
+__device__ __forceinline__ void decode_range(const AttnParams& p, float (&red)[4][HP][DecodeCfg<D>::PSTR], int tid, int lane,
+                                             int w, int kvh, int head0, int seq, int L, int qrow, int kstart, int kend,
+                                             int item) {
   using C = DecodeCfg<D>;
-  __shared__ float red[4][HP][C::PSTR];
-
-  const int bid = blockIdx.x;
-  const int kvh = bid % p.Hkv;
-  const int rest = bid / p.Hkv;
-  const int hg = rest % p.dec_hgroups;
-  const int turn = rest / p.dec_hgroups;
-  // the grid covers the whole item capacity, so the turn's records (longest chunks first) can be
-  // fetched together with the item count instead of after it
-  const WorkItem it = p.dec_items[2 * turn];
-  const int slot = p.dec_items[2 * turn + 1].x;
-  if (turn >= p.hdr->n_decode) return;
-  // the clamp only matters if the planner's capacity bound were ever violated
-  const int item = min(max(slot, 0), p.dec_cap - 1);
-  const int seq = it.x, chunk = it.y, L = it.z, qrow = it.w;
-  const int CH = p.hdr->chunk_keys;
-  const int kstart = chunk * CH;
-  const int kend = min(L, kstart + CH);
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int NW = 4;
   const int nblk = (kend - kstart + kBlock - 1) / kBlock;
-  const int bpw = (nblk + 3) / 4;
+  const int bpw = (nblk + NW - 1) / NW;
   const int b0 = min(w * bpw, nblk), b1 = min(b0 + bpw, nblk);
-  const int head0 = kvh * p.G + hg * HP;
 
   const __bf16* const qg = static_cast<const __bf16*>(p.q);
   const __bf16* const kg_ = static_cast<const __bf16*>(p.k_cache);
@@ -352,28 +334,128 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
   }
   __syncthreads();
 
-  // merge the 4 waves and write one partial record per head (8-bit cache: the value scale goes in here)
+  // merge the 4 waves and write one partial record per head
   const float vscale = KV8 ? p.v_scale[kvh] : 1.0f;
   for (int idx = tid; idx < HP * C::PSTR; idx += 256) {
     const int h = idx / C::PSTR, col = idx % C::PSTR;
-    float mm = fmaxf(fmaxf(red[0][h][D], red[1][h][D]), fmaxf(red[2][h][D], red[3][h][D]));
-    float out;
+    float mm = red[0][h][D];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) mm = fmaxf(mm, red[ww][h][D]);
+    float out = 0.0f;
     if (col == D) {
       out = mm;
     } else if (col < D + 2 + kMaxSpans) {
-      out = 0.0f;
 #pragma unroll
-      for (int ww = 0; ww < 4; ++ww) {
+      for (int ww = 0; ww < NW; ++ww) {
         const float mw = red[ww][h][D];
         const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - mm);
         out += e * red[ww][h][col];
       }
       if (KV8 && col < D) out *= vscale;
-    } else {
-      out = 0.0f;
     }
     p.partials[((size_t)item * p.Hq + head0 + h) * C::PSTR + col] = out;
   }
+}
+
+// SELF: the variant for batches of few single rows, where the planning launch is a large part of
+// the call.  Every sequence is cut into the same number of parts (p.dec_parts, chosen on the host so
+// that the grid fills the chip and the records fit the workspace) and a workgroup works out its own
+// part from the sequence length, so no planner runs: part 0 of a sequence also zero-fills the
+// sequence's `mass` entries and tells the merge kernel how many records to expect, and workgroup 0
+// writes the status word.
+template <int D, int HP, bool KV8, bool SELF>
+__global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
+  using C = DecodeCfg<D>;
+  constexpr int NW = 4;
+  __shared__ float red[NW][HP][C::PSTR];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int bid = blockIdx.x;
+  const int kvh = bid % p.Hkv;
+  const int rest = bid / p.Hkv;
+  const int hg = rest % p.dec_hgroups;
+  const int turn = rest / p.dec_hgroups;
+  const int head0 = kvh * p.G + hg * HP;
+  int seq, L, qrow, kstart, kend, item;
+  bool active = true;
+  // what this workgroup owes besides its part (SELF only; stores, so kept behind every load of the
+  // batch description: a store ahead of them would turn those scalar loads into vector loads)
+  bool owes_seq = false;      // zero-fill the sequence's `mass` entries of its heads, announce the record count
+  int n_records = 0;
+  auto settle = [&]() {
+    if constexpr (SELF) {
+      if (owes_seq) {
+        // (a reusing call keeps its promise of writing selected rows only; the merge kernel fills
+        // the selected entries in afterwards)
+        if (p.P > 0 && p.plan_fresh) {
+          const int per = p.NQ * p.S;
+          for (int ps = 0; ps < p.P; ++ps) {
+            const int ph = p.probe_heads[ps];
+            if (ph >= head0 && ph < head0 + HP)
+              for (int e = tid; e < per; e += 256) p.mass[((size_t)seq * p.P + ps) * per + e] = 0.0f;
+          }
+        }
+        if (kvh == 0 && hg == 0 && tid == 0) p.seq_dec[seq] = make_int2(seq * p.dec_parts, n_records);
+      }
+      if (bid == 0) {   // the status word a planner would have written: one pass over the batch
+        __shared__ int sh_status;
+        if (tid == 0) sh_status = 0;
+        __syncthreads();
+        const int max_ctx = p.max_blocks * kBlock;
+        int bits = 0;
+        for (int i = tid; i < p.num_seqs; i += 256) {
+          const int Li = p.seq_lens[i], r0 = p.cu_q_lens[i], ni = p.cu_q_lens[i + 1] - r0;
+          if (Li < 0 || ni < 0) { bits |= kStatNegative; continue; }
+          if (Li > max_ctx) bits |= kStatLenClamped;
+          if (ni > min(Li, max_ctx)) bits |= kStatQGtL;
+          else if (r0 < 0 || r0 + ni > p.total_q) bits |= kStatNegative;
+          else if (ni > 1) bits |= kStatHint;   // a row block in a batch promised to hold single rows
+        }
+        if (bits) atomicOr(&sh_status, bits);
+        __syncthreads();
+        if (tid == 0) { p.hdr->n_prefill = 0; p.hdr->n_decode = 0; p.hdr->chunk_keys = 0; p.hdr->status = sh_status; }
+      }
+    }
+  };
+  if constexpr (SELF) {
+    const int P = p.dec_parts;
+    seq = turn / P;
+    const int part = turn - seq * P;
+    const int Lraw = p.seq_lens[seq];
+    qrow = p.cu_q_lens[seq];
+    const int n = p.cu_q_lens[seq + 1] - qrow;
+    L = min(Lraw, p.max_blocks * kBlock);
+    const bool valid = Lraw >= 0 && n == 1 && L >= 1 && qrow >= 0 && qrow < p.total_q;
+    const int nblk_seq = valid ? (L + kBlock - 1) / kBlock : 0;
+    const int bpp = (nblk_seq + P - 1) / P;          // cache blocks per part
+    owes_seq = part == 0;
+    n_records = valid ? (nblk_seq + bpp - 1) / bpp : 0;
+    active = valid && part * bpp < nblk_seq;   // uniform over the workgroup
+    // (all of this is uniform over the workgroup; saying so keeps it out of the vector registers)
+    kstart = __builtin_amdgcn_readfirstlane(part * bpp * kBlock);
+    kend = __builtin_amdgcn_readfirstlane(min(L, kstart + bpp * kBlock));
+    L = __builtin_amdgcn_readfirstlane(L);
+    qrow = __builtin_amdgcn_readfirstlane(qrow);
+    seq = __builtin_amdgcn_readfirstlane(seq);
+    item = turn;
+  } else {
+    // the grid covers the whole item capacity, so the turn's records (longest chunks first) can be
+    // fetched together with the item count instead of after it
+    const WorkItem it = p.dec_items[2 * turn];
+    const int slot = p.dec_items[2 * turn + 1].x;
+    if (turn >= p.hdr->n_decode) return;
+    // the clamp only matters if the planner's capacity bound were ever violated
+    item = min(max(slot, 0), p.dec_cap - 1);
+    seq = it.x; L = it.z; qrow = it.w;
+    const int CH = p.hdr->chunk_keys;
+    kstart = it.y * CH;
+    kend = min(L, kstart + CH);
+  }
+
+  if (active) decode_range<D, HP, KV8>(p, red, tid, lane, w, kvh, head0, seq, L, qrow, kstart, kend, item);
+  settle();
 }
 
 // One workgroup per (sequence, 4 q heads): wave = head, lane = output columns.
@@ -468,8 +550,14 @@ hipError_t launch_decode_dh(const AttnParams& p, hipStream_t st) {
   const long long grid = (long long)p.dec_cap * p.Hkv * p.dec_hgroups;
   if (grid <= 0) return hipSuccess;
   if (!grid_fits(grid)) return hipErrorInvalidValue;
-  if (p.kv8) hipLaunchKernelGGL((k_decode<D, HP, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((k_decode<D, HP, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  if (p.dec_parts > 0) {   // self-planned: the grid is exact
+    const long long sgrid = (long long)p.num_seqs * p.dec_parts * p.Hkv * p.dec_hgroups;
+    if (p.kv8) hipLaunchKernelGGL((k_decode<D, HP, true, true>), dim3((unsigned)sgrid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((k_decode<D, HP, false, true>), dim3((unsigned)sgrid), dim3(256), 0, st, p);
+    return hipGetLastError();
+  }
+  if (p.kv8) hipLaunchKernelGGL((k_decode<D, HP, true, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((k_decode<D, HP, false, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

@@ -96,6 +96,8 @@ struct AttnParams {
   int dec_cap;
   int2* seq_dec;                    // per sequence {first decode item, number of chunks}
   float* partials;                  // [dec_cap, Hq, D + kPartialPad]
+  int dec_parts;                    // > 0: no planner; every single-row sequence is cut into this many parts
+  int plan_fresh;                   // the call promises a fully written `mass` (not a reused plan)
   // geometry chosen on the host from G
   int batch_kind;                   // 0 mixed, 1 no single-row sequences, 2 only single-row sequences
   int hpw;                          // q heads per prefill workgroup (4, 2 or 1)

@@ -439,7 +439,7 @@ def test_plan_reuse_across_layers():
 
 
 def test_batch_kind_hint():
-    """A correct hint changes nothing but the launches; a wrong one drops the contradicting
+    """A correct hint changes nothing but the launches (and, for few single rows, the split of the contexts); a wrong one drops the contradicting
     sequences (rows untouched, mass zero) and sets bit 3 of the status word."""
     from paper_2603_06588_amd import binding
     pre = W.random_batch(190, [300, 77, 150], [300, 2, 90], 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=3,
@@ -452,7 +452,13 @@ def test_batch_kind_hint():
         call.out.fill_(float("nan"))
         call.launch()
         torch.cuda.synchronize()
-        assert torch.equal(bits(call.out), bits(ref_out)) and torch.equal(bits(call.mass), bits(ref_mass))
+        if kind == binding.BATCH_PREFILL_ONLY:
+            assert torch.equal(bits(call.out), bits(ref_out)) and torch.equal(bits(call.mass), bits(ref_mass))
+        else:
+            # a small batch of single rows cuts its contexts into equal parts instead of planned chunks:
+            # the same sums in another order
+            assert torch.allclose(call.out.float(), ref_out.float(), atol=2e-2, rtol=2e-2)
+            assert torch.allclose(call.mass, ref_mass, atol=1e-3)
         assert call.device_status() == 0
         from paper_2603_06588_amd import benchlib
         ms = benchlib.launch_timed(call)
