@@ -147,6 +147,29 @@ def test_kv_write_quantises_into_fp8_cache_like_the_reference():
         assert int(diff.sum()) == 0, (got[diff][:8], want[diff][:8])
 
 
+def test_kv_write_quantises_every_bf16_pattern_like_the_reference():
+    """All 65536 bf16 bit patterns (NaNs, infinities, subnormals, both zeros included) as keys, and in
+    another order as values, under scales that are not powers of two."""
+    from oracle.capture import kv_write
+    from paper_2603_06588_amd import binding
+    b = W.random_batch(330, [512], [512], 2, 1, 128, torch.bfloat16, num_probe_heads=1, max_sel_q=1, poison=False)
+    b8 = W.fp8_cache_variant(b, 331, k_std=1.3, v_std=0.021)
+    pats = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    k_new = pats.view(torch.bfloat16).reshape(512, 1, 128).clone()
+    v_new = pats.roll(12345).view(torch.bfloat16).reshape(512, 1, 128).clone()
+    want_k, want_v = kv_write(k_new, v_new, b8.block_table, b8.seq_lens, b8.cu_q_lens, b8.k_cache, b8.v_cache,
+                              b8.k_scale, b8.v_scale)
+    bd = b8.to(DEV)
+    binding.hook_kv_write(k_new.to(DEV), v_new.to(DEV), bd.block_table, bd.seq_lens, bd.cu_q_lens, bd.k_cache,
+                          bd.v_cache, k_scale=bd.k_scale, v_scale=bd.v_scale)
+    torch.cuda.synchronize()
+    for got, want in ((bd.k_cache.cpu(), want_k), (bd.v_cache.cpu(), want_v)):
+        nan_w, nan_g = (want & 0x7F) == 0x7F, (got & 0x7F) == 0x7F
+        assert torch.equal(nan_w, nan_g)
+        diff = (got != want) & ~nan_w
+        assert int(diff.sum()) == 0, (got[diff][:8], want[diff][:8])
+
+
 @pytest.mark.parametrize("variant", ["bf16_mixed", "bf16_plan_reuse", "f32", "fp8_decode"])
 def test_attention_call_writes_the_new_rows_itself(variant):
     """k_new / v_new given to hook_attn_probe: the cache ends up as hook_kv_write leaves it and the results
