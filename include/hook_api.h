@@ -238,6 +238,8 @@ hook_status hook_attn_probe(const hook_attn_probe_args* args);
  *     HOOK_PLAN_FRESH call rewrites every word it later reads; HOOK_PLAN_REUSE reuses the lists
  *     of the previous static call on this GPU and is valid only if that call was for this batch.
  *   - hook_attn_probe_device_status cannot reach the array; use hook_attn_probe to debug.
+ *   - The first call on a GPU asks the runtime for the array's address on that GPU (once, kept per
+ *     device); make that call outside graph capture, as any warm-up call does.
  */
 #define HOOK_STATIC_SCRATCH_BYTES (16u << 20)
 hook_status hook_attn_probe_static(const hook_attn_probe_args* args);

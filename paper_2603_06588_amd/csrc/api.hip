@@ -333,6 +333,6 @@ const char* hook_status_string(hook_status s) {
   return "unknown status";
 }
 
-int hook_version(void) { return 1; }
+int hook_version(void) { return 2; }
 
 }  // extern "C"

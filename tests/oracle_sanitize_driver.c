@@ -19,6 +19,13 @@ int hook_oracle_attn_probe(int num_seqs, int total_q, int Hq, int Hkv, int d, in
                            const int32_t* block_table, const int32_t* seq_lens, const int32_t* cu_q_lens, int P,
                            const int32_t* probe_heads, int NQ, const int32_t* query_sel, int S,
                            const int32_t* key_spans, int n_rows, const int32_t* rows, double* out, double* mass);
+int hook_oracle_attn_probe_kv8(int num_seqs, int total_q, int Hq, int Hkv, int d, int B, int max_blocks, int num_blocks,
+                               int dtype, double scale, const void* q, const void* k_cache, const void* v_cache,
+                               const float* k_scale, const float* v_scale, const int32_t* block_table,
+                               const int32_t* seq_lens, const int32_t* cu_q_lens, int P, const int32_t* probe_heads,
+                               int NQ, const int32_t* query_sel, int S, const int32_t* key_spans, int n_rows,
+                               const int32_t* rows, double* out, double* mass);
+double hook_oracle_fp8_e4m3_value(uint8_t byte);
 int hook_oracle_steer(const void* hidden, const void* vec, float alpha, const uint8_t* token_mask, int T, int D,
                       int dtype, void* hidden_out);
 int hook_oracle_residual_steer(const void* hidden, const void* delta, const void* vec, float alpha,
@@ -123,6 +130,77 @@ static void run_attention(int dtype, int zero_q) {
   free(q); free(k); free(v); free(table); free(out); free(out2); free(mass);
 }
 
+/* The 8-bit cache: one byte per element, buffers exactly that large; q = 0 makes the output the
+ * prefix mean of the dequantised values, which is recomputed here from the byte decoder. */
+static void run_attention_kv8(void) {
+  const int lens[NSEQ] = {37, 5, 64, 0}, qn[NSEQ] = {1, 1, 1, 0};
+  int cu[NSEQ + 1] = {0};
+  int nblk_needed = 0, max_blocks = 0;
+  for (int i = 0; i < NSEQ; ++i) {
+    cu[i + 1] = cu[i] + qn[i];
+    const int nb = (lens[i] + B - 1) / B;
+    nblk_needed += nb;
+    if (nb > max_blocks) max_blocks = nb;
+  }
+  const int total_q = cu[NSEQ], num_blocks = nblk_needed + 2;
+  const size_t nq = (size_t)total_q * HQ * D, nkv = (size_t)num_blocks * HKV * B * D;
+  uint16_t* q = calloc(nq, sizeof(uint16_t));           /* q = 0 */
+  uint8_t* k = malloc(nkv);
+  uint8_t* v = malloc(nkv);
+  for (size_t e = 0; e < nkv; ++e) {
+    rnd();
+    k[e] = (uint8_t)(rng_state >> 40);
+    v[e] = (uint8_t)(rng_state >> 48);
+    if ((k[e] & 0x7F) == 0x7F) k[e] = 0x11;              /* live slots hold numbers */
+    if ((v[e] & 0x7F) == 0x7F) v[e] = 0x22;
+  }
+  int32_t* table = malloc(sizeof(int32_t) * (size_t)NSEQ * max_blocks);
+  int next = 0;
+  for (int i = 0; i < NSEQ; ++i)
+    for (int b = 0; b < max_blocks; ++b)
+      table[i * max_blocks + b] = b < (lens[i] + B - 1) / B ? next++ : 0x7FFFFFF0;
+  const float ks[HKV] = {0.37f, 2.0f}, vs[HKV] = {0.11f, 1.5f};
+  const int32_t heads[P] = {0, 3};
+  const int32_t sel[NSEQ * 2] = {0, 1, -1, 1, 0, 1, 0, 0};
+  int32_t spans[NSEQ * S * 2];
+  for (int i = 0; i < NSEQ; ++i) {
+    const int32_t sp[S * 2] = {0, lens[i], -3, 7, lens[i] - 2, lens[i] + 9, 6, 2};
+    memcpy(spans + i * S * 2, sp, sizeof sp);
+  }
+  double* out = malloc(sizeof(double) * nq);
+  double* mass = malloc(sizeof(double) * (size_t)NSEQ * P * NQ * S);
+  int rc = hook_oracle_attn_probe_kv8(NSEQ, total_q, HQ, HKV, D, B, max_blocks, num_blocks, 0, 0.25, q, k, v, ks, vs,
+                                      table, lens, cu, P, heads, NQ, sel, S, spans, 0, NULL, out, mass);
+  CHECK(rc == 0, "attn_probe_kv8 returned %d", rc);
+  for (int i = 0; i < NSEQ; ++i) {
+    if (qn[i] == 0) continue;
+    for (int h = 0; h < HQ; ++h) {
+      const int g = h / (HQ / HKV);
+      for (int e = 0; e < D; ++e) {
+        double mean = 0.0;
+        for (int j = 0; j < lens[i]; ++j) {
+          const int blk = table[i * max_blocks + j / B];
+          mean += (double)vs[g] * hook_oracle_fp8_e4m3_value(v[(((size_t)blk * HKV + g) * B + j % B) * D + e]);
+        }
+        mean /= lens[i];
+        const double got = out[((size_t)cu[i] * HQ + h) * D + e];
+        CHECK(fabs(got - mean) < 1e-12 * (1.0 + fabs(mean)), "kv8 seq %d head %d: %.17g vs %.17g", i, h, got, mean);
+      }
+    }
+    const int slot = -sel[2 * i];
+    for (int p = 0; p < P; ++p) {
+      const double* m = mass + (((size_t)i * P + p) * NQ + slot) * S;
+      CHECK(fabs(m[0] - 1.0) < 1e-12, "kv8 seq %d: whole-context mass %.17g", i, m[0]);
+      const int hi1 = 7 < lens[i] ? 7 : lens[i];
+      CHECK(fabs(m[1] - (double)hi1 / lens[i]) < 1e-12, "kv8 seq %d: clipped-low span %.17g", i, m[1]);
+    }
+  }
+  CHECK(hook_oracle_attn_probe_kv8(NSEQ, total_q, HQ, HKV, D, B, max_blocks, num_blocks, 0, 0.25, q, k, v, NULL, vs,
+                                   table, lens, cu, P, heads, NQ, sel, S, spans, 0, NULL, out, mass) == -1,
+        "missing scales accepted");
+  free(q); free(k); free(v); free(table); free(out); free(mass);
+}
+
 static void run_steering(int dtype) {
   enum { T = 7, DD = 24 };
   const size_t esz = dtype == 0 ? 2 : 4;
@@ -150,6 +228,7 @@ static void run_steering(int dtype) {
 int main(void) {
   for (int dtype = 0; dtype < 2; ++dtype)
     for (int zero_q = 0; zero_q < 2; ++zero_q) run_attention(dtype, zero_q);
+  run_attention_kv8();
   run_steering(0);
   run_steering(1);
   /* rounding helper on the values around a bf16 midpoint and at the ends of the range */

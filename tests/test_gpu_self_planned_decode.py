@@ -139,3 +139,34 @@ def test_self_planned_decode_reusing_call_writes_selected_entries_only():
     assert torch.equal(bits(call.out), bits(fresh.out))
     assert torch.equal(bits(call.mass[:, :, 0]), bits(fresh.mass[:, :, 0]))
     assert (call.mass[:, :, 1] == 5.0).all()          # slot 1 holds no row: never written by a reusing call
+
+
+@pytest.mark.parametrize("static_scratch", [False, True])
+def test_self_planned_decode_replays_from_a_hip_graph(static_scratch):
+    """The serving case this path is for: a captured decode step replayed several times, with eager work
+    and synchronisations in between, on a caller workspace and on the library's own scratch array."""
+    lens = [500, 33, 257, 1025, 1, 700, 90, 2100]
+    b = W.random_batch(1250, lens, [1] * len(lens), 32, 8, 128, torch.bfloat16, num_probe_heads=4, max_sel_q=1,
+                       max_spans=2)
+    b.query_sel[:, 0], b.query_sel[:, 1] = 0, 1
+    eager = _run(b)
+    call = binding.call_from_batch(b.to(DEV), batch_kind=binding.BATCH_DECODE_ONLY)
+    launch = call.launch_static if static_scratch else call.launch
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        launch(s)                       # warm-up on the side stream
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        launch(torch.cuda.current_stream())
+    for rep in range(3):
+        call.out.fill_(float("nan"))
+        call.mass.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bits(call.out), bits(eager.out)), rep
+        assert torch.equal(bits(call.mass), bits(eager.mass)), rep
+        again = _run(b)                 # eager work between the replays
+        assert torch.equal(bits(again.out), bits(eager.out))
