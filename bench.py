@@ -176,7 +176,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5,c6 (default: all)")
+    ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5,c6,d64 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-workload", default="", choices=["", "c2", "c3", "c3_fp8", "c4", "c5", "copy"],
                     help="only launch this workload --steps times (for rocprofv3 runs); prints no JSON. "
@@ -199,7 +199,7 @@ def main() -> int:
         return 2
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(x for x in args.only.split(",") if x) or {"c1", "c2", "c3", "c4", "c5", "c6"}
+    only = set(x for x in args.only.split(",") if x) or {"c1", "c2", "c3", "c4", "c5", "c6", "d64"}
     if args.profile_workload:
         wl = args.profile_workload
         steer = None
@@ -496,6 +496,32 @@ def main() -> int:
             "span_mass_overhead_pct": 100.0 * t6p["mean_ms"] / t6a["mean_ms"],
             "attention_tflops": attn_flops(b6) / (t6a["mean_ms"] * 1e-3) / 1e12}
         del b6, call6, mass6
+        torch.cuda.empty_cache()
+
+    if "d64" in only:
+        # head_dim 64 (bf16): the first-generation query-chunk kernel and the d = 64 instantiation of the
+        # single-row kernel, on C2- and C3-like batches, so that these paths carry a measured number too
+        gl = torch.Generator().manual_seed(11)
+        lens64 = [int(x) for x in torch.randint(512, 2049, (16,), generator=gl)]
+        bp = W.random_batch(11, lens64, lens64, 32, 8, 64, torch.bfloat16, std=64 ** -0.5, num_probe_heads=12,
+                            max_sel_q=8, max_spans=1, device=dev)
+        callp = binding.call_from_batch(bp, batch_kind=binding.BATCH_PREFILL_ONLY)
+        tp = time_call(callp.launch, K, Wm)
+        kp = kernel_times(callp, K)
+        dl = [int(x) for x in torch.randint(1024, 8193, (128,), generator=gl)]
+        bd = W.random_batch(12, dl, [1] * 128, 32, 8, 64, torch.bfloat16, std=64 ** -0.5, num_probe_heads=8,
+                            max_sel_q=1, max_spans=1, device=dev)
+        calld = binding.call_from_batch(bd, batch_kind=binding.BATCH_DECODE_ONLY)
+        td = time_call(calld.launch, K, Wm)
+        kd = kernel_times(calld, K)
+        extra["head_dim_64"] = {
+            "prefill": {"workload": "16 ragged prefills of 512-2048 tokens, 32 q / 8 kv heads, d 64, bf16",
+                        "ms_per_step": tp["mean_ms"], "kernels_ms": kp,
+                        "roofline": roofline_obj("mfma", "k_prefill<64>", attn_flops(bp), kp["prefill_ms"])},
+            "decode": {"workload": "128 single rows at 1024-8192 tokens of context, 32 q / 8 kv heads, d 64, bf16",
+                       "ms_per_step": td["mean_ms"], "kernels_ms": kd,
+                       "roofline": roofline_obj("hbm", "k_decode<64,4>", kv_bytes(bd), kd["decode_ms"])}}
+        del bp, bd, callp, calld
         torch.cuda.empty_cache()
 
     # ---- what the chip sustains: back-to-back MFMAs and a streaming read (measured last: the MFMA
