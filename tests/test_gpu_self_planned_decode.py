@@ -170,3 +170,44 @@ def test_self_planned_decode_replays_from_a_hip_graph(static_scratch):
         assert torch.equal(bits(call.mass), bits(eager.mass)), rep
         again = _run(b)                 # eager work between the replays
         assert torch.equal(bits(again.out), bits(eager.out))
+
+
+@pytest.mark.parametrize("group", [0, 1])
+def test_random_decode_only_batches(group):
+    """Seeded random single-row batches with the decode-only hint: head geometry, head_dim, number of
+    sequences on both sides of the self-planning limit, empty sequences, both cache types, probe set and
+    row selections (including ranges that begin before the row), against the oracle."""
+    import random
+    rng = random.Random(9500 + group)
+    for it in range(10):
+        G, Hkv = rng.choice([1, 2, 3, 4, 8]), rng.choice([1, 2, 4, 8])
+        d = rng.choice([128, 128, 64])
+        nseq = rng.choice([1, 3, 9, 40, 150])
+        lens = [rng.choice([rng.randint(1, 40), rng.randint(41, 300), rng.randint(300, 2500)]) for _ in range(nseq)]
+        qlens = [0 if rng.random() < 0.1 else 1 for _ in lens]
+        if sum(qlens) == 0:
+            qlens[0] = 1
+        nq = rng.choice([1, 2, 4])
+        b = W.random_batch(9600 + 100 * group + it, lens, qlens, G * Hkv, Hkv, d, torch.bfloat16,
+                           std=rng.choice([1.0, 1.0, 0.09]), num_probe_heads=rng.randint(1, G * Hkv), max_sel_q=nq,
+                           max_spans=rng.randint(1, 8))
+        for i in range(nseq):
+            begin = rng.choice([0, 0, 0, -1, 1, -(nq - 1)])
+            b.query_sel[i, 0], b.query_sel[i, 1] = begin, begin + rng.randint(0, nq + 1)
+        kv8 = rng.random() < 0.4
+        if kv8:
+            b = W.fp8_cache_variant(b, 9700 + it, k_std=rng.choice([1.0, 0.3]), v_std=1.0)
+        label = f"random decode g{group} #{it} nseq={nseq} Hq={G * Hkv} Hkv={Hkv} d={d} kv8={kv8}"
+        print(f"[case] {label}", flush=True)
+        bd = b.to(DEV)
+        out = torch.full_like(bd.q, float("nan"))
+        mass = torch.full((b.num_seqs, b.num_probe_heads, b.max_sel_q, b.max_spans), float("nan"), dtype=torch.float32,
+                          device=DEV)
+        call = binding.call_from_batch(bd, batch_kind=binding.BATCH_DECODE_ONLY, out=out, mass=mass)
+        call.launch()
+        torch.cuda.synchronize()
+        assert call.device_status() == 0, label
+        from helpers import valid_rows
+        written = torch.isfinite(out.float()).all(dim=2).all(dim=1).cpu()
+        assert bool((written == valid_rows(b)).all()), label
+        print("      ", compare_with_oracle(b, out, mass, label=label), flush=True)
