@@ -194,8 +194,9 @@ typedef struct hook_attn_probe_args {
 
   /* optional: the new tokens' keys and values, [total_q, Hkv, d] of `dtype`, device.  When both are
      given the call first writes them into k_cache / v_cache at positions L_i - n_i + t (exactly what
-     hook_kv_write does, quantising for an 8-bit cache), inside its first launch, and only then reads
-     the caches: the one place where the call writes through k_cache / v_cache. */
+     hook_kv_write does, quantising for an 8-bit cache) and only then reads the caches - inside the
+     planning launch where the call has one, else in a launch of its own ahead of the attention
+     kernels: the one place where the call writes through k_cache / v_cache. */
   const void*  k_new;
   const void*  v_new;
 } hook_attn_probe_args;
@@ -212,8 +213,10 @@ size_t hook_attn_probe_workspace_bytes(const hook_attn_probe_args* args);
  * waiting.  Sequences with one query row take a split-key decode path whose
  * partial results are merged by a combine kernel; longer chunks take the tiled
  * prefill path; both may be mixed in one call.  Results are deterministic: the
- * same inputs give bit-identical `out` and `mass` on every call, for any
- * physical block permutation, and `out` does not depend on the probe arguments.
+ * same inputs (batch_kind included: a hint may change how single rows are split,
+ * which changes the order of the sums) give bit-identical `out` and `mass` on
+ * every call, for any physical block permutation, and `out` does not depend on
+ * the probe arguments.
  * HOOK_F32 inputs take one full-precision kernel that needs no work lists: batch_kind and plan_mode
  * are ignored for them (every valid sequence is computed and `mass` is zero-filled on every call);
  * the status word is written as for bf16 (bits 0-2).
