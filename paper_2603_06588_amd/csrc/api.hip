@@ -105,8 +105,10 @@ namespace hook {
 // Validates, carves the workspace and launches.  With `ev` (5 events) the launches are
 // bracketed by event records so a profiling caller can read per-kernel durations (used by the
 // separate measurement library, which links these objects; not part of the exported ABI).
-__attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev,
-                                                                 void* workspace, size_t workspace_bytes) {
+// Everything about a call that the host can check without its workspace.  HOOK_OK with *nothing_to_do
+// set means a valid call that has no work (no sequences or no rows).
+__attribute__((visibility("hidden"))) hook_status check_attn_probe_args(const hook_attn_probe_args* a, bool* nothing_to_do) {
+  *nothing_to_do = false;
   if (!a) return HOOK_ERR_NULL;
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
@@ -126,11 +128,21 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   const bool kv8 = a->kv_dtype == HOOK_KV_FP8_E4M3;
   // the 8-bit cache is read by the single-row kernels only, with bf16 queries
   if (kv8 && (a->dtype != HOOK_BF16 || a->batch_kind != HOOK_BATCH_DECODE_ONLY)) return HOOK_ERR_UNSUPPORTED;
-  if (a->num_seqs == 0 || a->total_q == 0) return HOOK_OK;
+  if (a->num_seqs == 0 || a->total_q == 0) { *nothing_to_do = true; return HOOK_OK; }
   if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
     return HOOK_ERR_NULL;
   if (kv8 && (!a->k_scale || !a->v_scale)) return HOOK_ERR_NULL;
   if ((a->k_new == nullptr) != (a->v_new == nullptr)) return HOOK_ERR_NULL;
+  return HOOK_OK;
+}
+
+__attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn_probe_args* a, hipEvent_t* ev,
+                                                                 void* workspace, size_t workspace_bytes) {
+  bool nothing_to_do = false;
+  const hook_status checked = check_attn_probe_args(a, &nothing_to_do);
+  if (checked != HOOK_OK || nothing_to_do) return checked;
+  const int P = a->num_probe_heads;
+  const bool kv8 = a->kv_dtype == HOOK_KV_FP8_E4M3;
   const Layout l = make_layout(a);
   // one-dimensional launch grids over the item capacities
   if (a->dtype == HOOK_BF16 &&
@@ -247,9 +259,11 @@ void* scratch_on_current_device() {
 size_t hook_attn_probe_static_capacity(void) { return (size_t)HOOK_STATIC_SCRATCH_BYTES; }
 
 hook_status hook_attn_probe_static(const hook_attn_probe_args* a) {
-  if (!a) return HOOK_ERR_NULL;
-  // the size check comes first so that an oversized call is refused without touching the device
-  if (shapes_supported(a) && make_layout(a).total > (size_t)HOOK_STATIC_SCRATCH_BYTES) return HOOK_ERR_WORKSPACE;
+  // the argument and size checks come first, so that a call that is refused never touches the device
+  bool nothing_to_do = false;
+  const hook_status checked = hook::check_attn_probe_args(a, &nothing_to_do);
+  if (checked != HOOK_OK || nothing_to_do) return checked;
+  if (make_layout(a).total > (size_t)HOOK_STATIC_SCRATCH_BYTES) return HOOK_ERR_WORKSPACE;
   void* ws = scratch_on_current_device();
   if (!ws) return HOOK_ERR_LAUNCH;
   return run_attn_probe(a, nullptr, ws, (size_t)HOOK_STATIC_SCRATCH_BYTES);

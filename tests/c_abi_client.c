@@ -17,11 +17,19 @@ int main(void) {
   memset(&w, 0, sizeof w);
   memset(&r, 0, sizeof r);
 
-  fails += hook_version() < 1;
+  fails += hook_version() < 2;
   fails += strcmp(hook_status_string(HOOK_OK), "ok") != 0;
   fails += hook_attn_probe(NULL) != HOOK_ERR_NULL;
   fails += hook_attn_probe(&a) != HOOK_ERR_SHAPE;          /* zero heads */
   fails += hook_attn_probe_workspace_bytes(&a) != 0;
+  fails += hook_attn_probe_static(NULL) != HOOK_ERR_NULL;
+  fails += hook_attn_probe_static(&a) != HOOK_ERR_SHAPE;   /* the same argument checks, before anything else */
+  fails += hook_attn_probe_static_capacity() != HOOK_STATIC_SCRATCH_BYTES;
+  a.kv_dtype = HOOK_KV_FP8_E4M3;                           /* the fields of the 8-bit cache and of the */
+  a.k_scale = a.v_scale = NULL;                            /* in-call cache write are part of the struct */
+  a.k_new = a.v_new = NULL;
+  fails += hook_attn_probe(&a) != HOOK_ERR_SHAPE;          /* still rejected for its shapes first */
+  a.kv_dtype = HOOK_KV_SAME;
   fails += hook_attn_probe_validate(NULL, &count) != HOOK_ERR_NULL;
   fails += hook_span_mass(NULL) != HOOK_ERR_NULL;
   fails += hook_span_mass_workspace_bytes(NULL) != 0;
