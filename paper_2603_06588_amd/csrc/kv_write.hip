@@ -1,5 +1,5 @@
 // Scatter of the new tokens' K and V rows into the paged cache (stand-alone launch; the attention
-// call can do the same inside its planning launch).  A workgroup takes 16 consecutive rows of
+// call can do the same inside its planning launch).  A workgroup takes 8 consecutive rows of
 // k_new / v_new; the tile code is in kv_write_device.h.
 #include "../../include/hook_api.h"
 #include "kv_write_device.h"
