@@ -338,6 +338,21 @@ def main() -> int:
         del bs, calls, calls_reuse
         torch.cuda.empty_cache()
 
+    if "c2" in only:
+        # one prompt on its own (the paper's detection use case: a single prompt, probed at its last token):
+        # the call is bound by the longest row block's walk over the keys, not by throughput
+        b1p = W.random_batch(21, [2048], [2048], 32, 8, 128, torch.bfloat16, std=128 ** -0.5, num_probe_heads=8,
+                             max_sel_q=1, max_spans=2, device=dev)
+        call1p = binding.call_from_batch(b1p, batch_kind=binding.BATCH_PREFILL_ONLY)
+        t1p = time_batch(call1p.launch, 4 * K, Wm)
+        k1p = kernel_times(call1p, K)
+        extra["single_prompt_2048"] = {
+            "workload": "one prefill of 2048 tokens, 32 q / 8 kv heads, d 128, 8 probed heads, last row",
+            "us_per_call_back_to_back": t1p * 1e3, "kernels_ms": k1p,
+            "roofline": roofline_obj("mfma", "k_prefill128", attn_flops(b1p), k1p["prefill_ms"])}
+        del b1p, call1p
+        torch.cuda.empty_cache()
+
     if "c4" in only:
         b4 = W.c4_long_prefill_70b(device=dev)
         call4 = binding.call_from_batch(b4, batch_kind=binding.BATCH_PREFILL_ONLY)
