@@ -83,7 +83,9 @@ typedef enum { HOOK_KV_SAME = 0, HOOK_KV_FP8_E4M3 = 1 } hook_kv_dtype;
  * triples, i.e. up to 64 sequences at 8 kv heads) plans itself: every sequence is cut into the same
  * number of parts, the workgroups read the lengths themselves and the planning launch is left out
  * (two launches instead of three).  Results are the same to rounding order; the status word is
- * written as always.
+ * written as always.  A HOOK_BATCH_PREFILL_ONLY call that holds ONE sequence (a single prompt;
+ * HOOK_BF16, head_dim 128) needs no planning launch either: the chunk kernel works out its row
+ * blocks itself, with results bit for bit those of the planned call.
  */
 typedef enum hook_batch_kind {
   HOOK_BATCH_MIXED = 0,         /* anything (default) */

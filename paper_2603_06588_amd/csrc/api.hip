@@ -198,13 +198,15 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   p.dec_hp = l.dec_hp; p.dec_hgroups = l.dec_hgroups;
   p.batch_kind = a->batch_kind;
   p.dec_parts = self_plan_parts(a, l);
+  // a single prompt on its own needs no planner either (head_dim 128: the kernel that can plan for itself)
+  p.pf_self = a->dtype == HOOK_BF16 && a->head_dim == 128 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY && a->num_seqs == 1;
   p.plan_fresh = a->plan_mode == HOOK_PLAN_FRESH;
 
   hipStream_t st = static_cast<hipStream_t>(a->stream);
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
   if (!mark(0)) return HOOK_ERR_LAUNCH;
   // the planning launch carries the cache write; where there is no such launch it gets its own
-  if (writes_kv && (a->dtype == HOOK_F32 || a->plan_mode == HOOK_PLAN_REUSE || p.dec_parts > 0) &&
+  if (writes_kv && (a->dtype == HOOK_F32 || a->plan_mode == HOOK_PLAN_REUSE || p.dec_parts > 0 || p.pf_self) &&
       launch_kv_write(p.kvw, st) != hipSuccess)
     return HOOK_ERR_LAUNCH;
   if (a->dtype == HOOK_F32) {
@@ -215,7 +217,7 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   }
   // a reusing call finds the work lists of the same batch in the workspace; a self-planned batch
   // of single rows needs none
-  if ((a->plan_mode == HOOK_PLAN_FRESH && p.dec_parts == 0 && launch_plan(p, st) != hipSuccess) || !mark(1))
+  if ((a->plan_mode == HOOK_PLAN_FRESH && p.dec_parts == 0 && !p.pf_self && launch_plan(p, st) != hipSuccess) || !mark(1))
     return HOOK_ERR_LAUNCH;
   const bool chunks = a->batch_kind != HOOK_BATCH_DECODE_ONLY, singles = a->batch_kind != HOOK_BATCH_PREFILL_ONLY;
   if ((chunks && launch_prefill(p, a->head_dim, st) != hipSuccess) || !mark(2)) return HOOK_ERR_LAUNCH;

@@ -98,6 +98,7 @@ struct AttnParams {
   float* partials;                  // [dec_cap, Hq, D + kPartialPad]
   int dec_parts;                    // > 0: no planner; every single-row sequence is cut into this many parts
   int plan_fresh;                   // the call promises a fully written `mass` (not a reused plan)
+  int pf_self;                      // one sequence of query rows, head_dim 128: the chunk kernel plans itself
   // geometry chosen on the host from G
   int batch_kind;                   // 0 mixed, 1 no single-row sequences, 2 only single-row sequences
   int hpw;                          // q heads per prefill workgroup (4, 2 or 1)

@@ -444,21 +444,13 @@ __device__ __forceinline__ void run_tiles(const WaveCtx& cx, unsigned char* smem
                                       l_run, am, sp_a, sp_b);
 }
 
-__global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-  const int bid = blockIdx.x;
-  const int kvh = bid % p.Hkv;
-  const int rest = bid / p.Hkv;
-  const int hg = rest % p.hgroups;
-  const int item = rest / p.hgroups;
-  // the grid covers the whole item capacity, so both records can be fetched together with
-  // the item count instead of after it
-  const WorkItem it = p.pf_items[2 * item];
-  const int qbase = p.pf_items[2 * item + 1].x;
-  if (item >= p.hdr->n_prefill) return;
-  const int seq = it.x, row0 = it.y, L = it.z, n = it.w;
-
+// One work item: rows [row0, row0 + rows_per_wg) of sequence `seq` (context L, n rows, first q row
+// qbase) for the heads of (kvh, hg).  ZERO_REST (self-planned call only): the wave that owns a probed
+// head in the item of row 0 also writes zeros to that head's `mass` slots that hold no row, so that
+// every entry of `mass` is written exactly once without a planner's zero-fill.
+template <bool ZERO_REST>
+__device__ __forceinline__ void prefill128_item(const AttnParams& p, unsigned char* smem, int kvh, int hg, int seq,
+                                                int row0, int L, int n, int qbase) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -590,18 +582,79 @@ __global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
       }
     }
   }
+  if constexpr (ZERO_REST) {
+    if (row0 == 0 && rb == 0 && pslot >= 0 && p.plan_fresh) {
+      const int lo = max(qsel_b, 0), hi = min(qsel_e, n);     // slots lo - qsel_b .. hi - qsel_b - 1 hold rows
+      for (int e = lane; e < p.NQ * p.S; e += 64) {
+        const int tr = qsel_b + e / p.S;
+        if (tr < lo || tr >= hi) p.mass[((size_t)seq * p.P + pslot) * p.NQ * p.S + e] = 0.0f;
+      }
+    }
+  }
+}
+
+// PLANNED: the work item comes from the planner's list.  Otherwise the call holds ONE sequence and
+// plans itself (no planning launch, which is a sixth of a 2048-token prompt's call): the row blocks are
+// taken last block first (longest first), workgroup 0 writes the status word, and `mass` is written
+// entry by entry by the waves that own the entries.  All stores sit behind the body, so that the loads
+// of the batch description stay scalar loads.
+template <bool PLANNED>
+__global__ __launch_bounds__(256, 2) void k_prefill128(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int bid = blockIdx.x;
+  const int kvh = bid % p.Hkv;
+  const int rest = bid / p.Hkv;
+  const int hg = rest % p.hgroups;
+  const int item = rest / p.hgroups;
+  if constexpr (PLANNED) {
+    // the grid covers the whole item capacity, so both records can be fetched together with
+    // the item count instead of after it
+    const WorkItem it = p.pf_items[2 * item];
+    const int qbase = p.pf_items[2 * item + 1].x;
+    if (item >= p.hdr->n_prefill) return;
+    prefill128_item<false>(p, smem, kvh, hg, it.x, it.y, it.z, it.w, qbase);
+  } else {
+    const int max_ctx = p.max_blocks * kBlock;
+    const int Lraw = p.seq_lens[0], qbase = p.cu_q_lens[0], n = p.cu_q_lens[1] - qbase;
+    const int L = min(Lraw, max_ctx);
+    int status = 0;
+    bool valid = false;
+    if (Lraw < 0 || n < 0) status = kStatNegative;
+    else {
+      if (Lraw > max_ctx) status |= kStatLenClamped;
+      if (n > L) status |= kStatQGtL;
+      else if (qbase < 0 || qbase + n > p.total_q) status |= kStatNegative;
+      else if (n == 1) status |= kStatHint;      // a single row in a call promised to hold chunks: dropped
+      else valid = n >= 2;
+    }
+    const int nitems = valid ? (n + p.rows_per_wg - 1) / p.rows_per_wg : 0;
+    if (item < nitems)
+      prefill128_item<true>(p, smem, kvh, hg, 0, (nitems - 1 - item) * p.rows_per_wg, L, n, qbase);
+    if (bid == 0) {
+      if (threadIdx.x == 0) { p.hdr->n_prefill = nitems; p.hdr->n_decode = 0; p.hdr->chunk_keys = 0; p.hdr->status = status; }
+      if (!valid && p.plan_fresh)     // nothing ran: every entry of `mass` is zero
+        for (int e = threadIdx.x; e < p.P * p.NQ * p.S; e += 256) p.mass[e] = 0.0f;
+    }
+  }
 }
 
 }  // namespace
 
 hipError_t launch_prefill128(const AttnParams& p, hipStream_t st) {
-  static std::atomic<unsigned long long> configured{0};
-  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill128), kLdsBytes, configured);
-  if (e != hipSuccess) return e;
+  static std::atomic<unsigned long long> configured{0}, configured_self{0};
   const long long grid = (long long)p.pf_cap * p.Hkv * p.hgroups;
   if (grid <= 0) return hipSuccess;
   if (!grid_fits(grid)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_prefill128, dim3((unsigned)grid), dim3(256), kLdsBytes, st, p);
+  if (p.pf_self) {
+    const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill128<false>), kLdsBytes, configured_self);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_prefill128<false>, dim3((unsigned)grid), dim3(256), kLdsBytes, st, p);
+    return hipGetLastError();
+  }
+  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill128<true>), kLdsBytes, configured);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_prefill128<true>, dim3((unsigned)grid), dim3(256), kLdsBytes, st, p);
   return hipGetLastError();
 }
 
