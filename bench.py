@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # until the counters are taken again.
 TRAFFIC = {
     # key: (bytes per launch, source files, hash of those files when the counters were taken)
-    "k_prefill128/c2": (797612708, ("prefill128.hip", "hook_device.h"), "5d23cc41f9f0ed04"),
-    "k_prefill128/c4": (5190593903, ("prefill128.hip", "hook_device.h"), "5d23cc41f9f0ed04"),
-    "k_decode/c3": (4911382943, ("decode.hip", "hook_device.h"), "d251888f04e07d93"),
-    "k_decode/c3_fp8": (2439330116, ("decode.hip", "hook_device.h"), "d251888f04e07d93"),
+    "k_prefill128/c2": (797424994, ("prefill128.hip", "hook_device.h"), "2a8a49143a6fb91c"),
+    "k_prefill128/c4": (5191965184, ("prefill128.hip", "hook_device.h"), "2a8a49143a6fb91c"),
+    "k_decode/c3": (4910675161, ("decode.hip", "hook_device.h"), "6a4b00fc927a5ed1"),
+    "k_decode/c3_fp8": (2440025513, ("decode.hip", "hook_device.h"), "6a4b00fc927a5ed1"),
 }
 
 

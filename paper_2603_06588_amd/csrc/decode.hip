@@ -47,7 +47,7 @@ __device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w, bool upper_half)
 // blocks, merge in LDS and leave one partial record per head in slot `item`.
 template <int D, int HP, bool KV8>
 __device__ __forceinline__ void decode_range(const AttnParams& p, float (&red)[4][HP][DecodeCfg<D>::PSTR], int tid, int lane,
-                                             int w, int kvh, int head0, int seq, int L, int qrow, int kstart, int kend,
+                                             int w, int kvh, int head0, int seq, int qrow, int kstart, int kend,
                                              int item) {
   using C = DecodeCfg<D>;
   constexpr int NW = 4;
@@ -436,7 +436,6 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
     // (all of this is uniform over the workgroup; saying so keeps it out of the vector registers)
     kstart = __builtin_amdgcn_readfirstlane(part * bpp * kBlock);
     kend = __builtin_amdgcn_readfirstlane(min(L, kstart + bpp * kBlock));
-    L = __builtin_amdgcn_readfirstlane(L);
     qrow = __builtin_amdgcn_readfirstlane(qrow);
     seq = __builtin_amdgcn_readfirstlane(seq);
     item = turn;
@@ -454,7 +453,7 @@ __global__ __launch_bounds__(256) void k_decode(const AttnParams p) {
     kend = min(L, kstart + CH);
   }
 
-  if (active) decode_range<D, HP, KV8>(p, red, tid, lane, w, kvh, head0, seq, L, qrow, kstart, kend, item);
+  if (active) decode_range<D, HP, KV8>(p, red, tid, lane, w, kvh, head0, seq, qrow, kstart, kend, item);
   settle();
 }
 
