@@ -65,10 +65,12 @@ typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
  * HOOK_KV_FP8_E4M3: one byte per element in the 8-bit E4M3 format (1 sign, 4 exponent, 3 mantissa
  * bits, bias 7, no infinities, NaN = S.1111.111); the element a byte stands for is its value times
  * the fp32 scale of its kv head: K[j][c] = value(k_cache byte) * k_scale[g], V alike with v_scale.
- * Supported where it pays, on the bandwidth-bound path: batches of single-row sequences
- * (batch_kind = HOOK_BATCH_DECODE_ONLY is then required) with HOOK_BF16 queries; the cache layout
- * stays [num_blocks, Hkv, B, d] with one byte per element.  The paper does not discuss cache
- * precision; this is the usual serving option of halving the bytes a decode step streams.
+ * Needs HOOK_BF16 queries; the cache layout stays [num_blocks, Hkv, B, d] with one byte per
+ * element.  Any batch is served: single rows stream the bytes as they are (the bandwidth-bound
+ * case the format pays for), query chunks widen them to bf16 on their way into local memory, so a
+ * chunked prefill can run on the same cache.  hook_span_mass does not take it.  The paper does not
+ * discuss cache precision; this is the usual serving option of halving the bytes a decode step
+ * streams.
  */
 typedef enum { HOOK_KV_SAME = 0, HOOK_KV_FP8_E4M3 = 1 } hook_kv_dtype;
 

@@ -126,8 +126,8 @@ __attribute__((visibility("hidden"))) hook_status check_attn_probe_args(const ho
   }
   if (a->kv_dtype != HOOK_KV_SAME && a->kv_dtype != HOOK_KV_FP8_E4M3) return HOOK_ERR_SHAPE;
   const bool kv8 = a->kv_dtype == HOOK_KV_FP8_E4M3;
-  // the 8-bit cache is read by the single-row kernels only, with bf16 queries
-  if (kv8 && (a->dtype != HOOK_BF16 || a->batch_kind != HOOK_BATCH_DECODE_ONLY)) return HOOK_ERR_UNSUPPORTED;
+  // the 8-bit cache goes with bf16 queries
+  if (kv8 && a->dtype != HOOK_BF16) return HOOK_ERR_UNSUPPORTED;
   if (a->num_seqs == 0 || a->total_q == 0) { *nothing_to_do = true; return HOOK_OK; }
   if (!a->q || !a->k_cache || !a->v_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens || !a->out)
     return HOOK_ERR_NULL;
@@ -199,7 +199,8 @@ __attribute__((visibility("hidden"))) hook_status run_attn_probe(const hook_attn
   p.batch_kind = a->batch_kind;
   p.dec_parts = self_plan_parts(a, l);
   // a single prompt on its own needs no planner either (head_dim 128: the kernel that can plan for itself)
-  p.pf_self = a->dtype == HOOK_BF16 && a->head_dim == 128 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY && a->num_seqs == 1;
+  p.pf_self = a->dtype == HOOK_BF16 && a->head_dim == 128 && !kv8 && a->batch_kind == HOOK_BATCH_PREFILL_ONLY &&
+              a->num_seqs == 1;
   p.plan_fresh = a->plan_mode == HOOK_PLAN_FRESH;
 
   hipStream_t st = static_cast<hipStream_t>(a->stream);

@@ -12,6 +12,13 @@
 // B operand of O^T = V^T P^T without touching LDS.  Probe span sums are accumulated from
 // the fp32 exponentials under the same running reference as the normaliser and divided by
 // it at the end, so the captured mass is the exact softmax mass.
+//
+// KV8: the caches hold 8-bit E4M3 bytes with one fp32 scale per kv head.  Tiles are staged through
+// registers here, so the bytes are widened to bf16 (exactly: every E4M3 number is a bf16 number) on
+// their way into LDS and the loop itself does not change; the key scale is folded into the softmax
+// scale and the value scale into the final normalisation of `out`.  This is what serves query chunks
+// over an 8-bit cache for both head dimensions (the direct-to-LDS kernel for head_dim 128 cannot
+// convert on the way).
 #include "hook_device.h"
 
 namespace hook {
@@ -38,7 +45,21 @@ __device__ __forceinline__ int vt_group_pos(int kg) {
   return 16 * (kg >> 2) + 8 * (kg & 1) + 4 * ((kg >> 1) & 1);
 }
 
-template <int D>
+// eight E4M3 bytes (two words) -> eight bf16 values
+__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint2 raw) {
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.x, 1.0f, false);
+  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.x, 1.0f, true);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.y, 1.0f, false);
+  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.y, 1.0f, true);
+  uint4 v;
+  __builtin_memcpy(&v.x, &a, 4);
+  __builtin_memcpy(&v.y, &b, 4);
+  __builtin_memcpy(&v.z, &c, 4);
+  __builtin_memcpy(&v.w, &d, 4);
+  return v;
+}
+
+template <int D, bool KV8>
 __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
   using C = PrefillCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -75,6 +96,8 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
   const __bf16* const qg = static_cast<const __bf16*>(p.q);
   const __bf16* const kg_ = static_cast<const __bf16*>(p.k_cache);
   const __bf16* const vg_ = static_cast<const __bf16*>(p.v_cache);
+  const unsigned char* const kg8 = static_cast<const unsigned char*>(p.k_cache);
+  const unsigned char* const vg8 = static_cast<const unsigned char*>(p.v_cache);
   const int* const bt = p.block_table + (size_t)seq * p.max_blocks;
   const size_t blk_stride = (size_t)p.Hkv * kBlock * D;        // elements per block
   const size_t head_off = (size_t)kvh * kBlock * D;
@@ -124,7 +147,9 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
       if (key < L) {
         int blk = bt[key >> 4];
         blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
-        v = *reinterpret_cast<const uint4*>(kg_ + (size_t)blk * blk_stride + head_off + (size_t)(key & 15) * D + 8 * k_ch);
+        const size_t off = (size_t)blk * blk_stride + head_off + (size_t)(key & 15) * D + 8 * k_ch;   // in elements
+        if constexpr (KV8) v = e4m3x8_to_bf16x8(*reinterpret_cast<const uint2*>(kg8 + off));
+        else v = *reinterpret_cast<const uint4*>(kg_ + off);
       }
       kreg[j] = v;
     }
@@ -135,11 +160,14 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
         blk = bt[kbase >> 4];
         blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
       }
-      const __bf16* vp = vg_ + (size_t)blk * blk_stride + head_off + (size_t)(kbase & 15) * D + 8 * v_dc;
+      const size_t voff = (size_t)blk * blk_stride + head_off + (size_t)(kbase & 15) * D + 8 * v_dc;   // in elements
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (kbase + i < L) v = *reinterpret_cast<const uint4*>(vp + (size_t)i * D);
+        if (kbase + i < L) {
+          if constexpr (KV8) v = e4m3x8_to_bf16x8(*reinterpret_cast<const uint2*>(vg8 + voff + (size_t)i * D));
+          else v = *reinterpret_cast<const uint4*>(vg_ + voff + (size_t)i * D);
+        }
         vreg[i] = v;
       }
     }
@@ -180,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
   float am[kMaxSpans];
 #pragma unroll
   for (int s = 0; s < kMaxSpans; ++s) am[s] = 0.0f;
-  const float c = p.scale_log2;
+  const float c = KV8 ? p.scale_log2 * p.k_scale[kvh] : p.scale_log2;
 
   load_tile(0);
   store_tile(0);
@@ -294,7 +322,8 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
 
   // epilogue: normalise, transpose through LDS (the K buffers are free now), coalesced stores
   const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = 1.0f / l_tot;
+  const float inv_l = 1.0f / l_tot;
+  const float inv = KV8 ? inv_l * p.v_scale[kvh] : inv_l;     // `out` carries the value scale, `mass` does not
   __bf16* const ot = Ks + w * (kWaveRows * C::KSTR);
   if (wave_active) {
 #pragma unroll
@@ -328,31 +357,36 @@ __global__ __launch_bounds__(256, 2) void k_prefill(const AttnParams p) {
           const float a_tot = am[s] + __shfl_xor(am[s], 32);
           const int tr = wrow0 + qi;
           if (hf == 0 && tr < n && tr >= qsel_b && tr < qsel_e)
-            p.mass[(((size_t)seq * p.P + pslot) * p.NQ + (tr - qsel_b)) * p.S + s] = a_tot * inv;
+            p.mass[(((size_t)seq * p.P + pslot) * p.NQ + (tr - qsel_b)) * p.S + s] = a_tot * inv_l;
         }
       }
     }
   }
 }
 
-template <int D>
+template <int D, bool KV8>
 hipError_t launch_prefill_d(const AttnParams& p, hipStream_t st) {
   using C = PrefillCfg<D>;
   static std::atomic<unsigned long long> configured{0};
-  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill<D>), (int)C::LDS_BYTES, configured);
+  const hipError_t e = raise_lds_limit_once(reinterpret_cast<const void*>(&k_prefill<D, KV8>), (int)C::LDS_BYTES, configured);
   if (e != hipSuccess) return e;
   const long long grid = (long long)p.pf_cap * p.Hkv * p.hgroups;
   if (grid <= 0) return hipSuccess;
   if (!grid_fits(grid)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_prefill<D>, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, p);
+  hipLaunchKernelGGL((k_prefill<D, KV8>), dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_prefill(const AttnParams& p, int D, hipStream_t st) {
+  if (p.kv8) {   // 8-bit caches: the register-staged kernel, which widens the bytes on their way into LDS
+    if (D == 128) return launch_prefill_d<128, true>(p, st);
+    if (D == 64) return launch_prefill_d<64, true>(p, st);
+    return hipErrorInvalidValue;
+  }
   if (D == 128) return launch_prefill128(p, st);
-  if (D == 64) return launch_prefill_d<64>(p, st);
+  if (D == 64) return launch_prefill_d<64, false>(p, st);
   return hipErrorInvalidValue;
 }
 

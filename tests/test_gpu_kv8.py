@@ -1,5 +1,6 @@
-"""Single-row (decode) attention over an 8-bit E4M3 key/value cache against the CPU oracle, through
-the C ABI (needs an MI355X).  The oracle dequantises every byte and runs the plain definition."""
+"""Attention over an 8-bit E4M3 key/value cache against the CPU oracle, through the C ABI (needs an
+MI355X): single rows (the bandwidth-bound case the format is for), query chunks and mixed batches.  The
+oracle dequantises every byte and runs the plain definition."""
 import ctypes
 
 import pytest
@@ -100,7 +101,7 @@ def test_fp8_cache_argument_checks():
     b = W.random_batch(970, [100, 50], [1, 1], 8, 2, 128, torch.bfloat16, num_probe_heads=2)
     b8 = W.fp8_cache_variant(b, 971).to(DEV)
     call = binding.call_from_batch(b8, batch_kind=binding.BATCH_MIXED)
-    assert lib.hook_attn_probe(ctypes.byref(call.args)) == 3       # needs the decode-only hint
+    assert lib.hook_attn_probe(ctypes.byref(call.args)) == 0       # any composition of the batch is served
     call = binding.call_from_batch(b8, batch_kind=binding.BATCH_DECODE_ONLY)
     call.args.k_scale = 0
     assert lib.hook_attn_probe(ctypes.byref(call.args)) == 1       # scales missing
@@ -108,3 +109,74 @@ def test_fp8_cache_argument_checks():
     call.args.kv_dtype = 7
     assert lib.hook_attn_probe(ctypes.byref(call.args)) == 2
     assert lib.hook_span_mass(ctypes.byref(binding.call_from_batch(b8, batch_kind=2).args)) == 3
+
+
+CHUNK_CASES = [
+    # seed, context lengths, query rows, Hq, Hkv, d, key std, value std
+    (981, [200], [200], 8, 2, 128, 1.0, 1.0),                       # one prompt, 4 tiles, G = 4
+    (982, [77, 130, 65, 64], [77, 130, 65, 64], 8, 2, 128, 1.0, 1.0),   # ragged, tile-edge lengths
+    (983, [300, 150], [45, 150], 8, 2, 128, 1.0, 0.7),              # a chunk on prior context
+    (984, [700, 90, 1, 260], [1, 90, 1, 3], 8, 2, 128, 1.0, 1.0),   # single rows, chunks and a tiny chunk together
+    (985, [190, 64], [190, 64], 8, 1, 128, 0.5, 1.0),               # G = 8
+    (986, [150, 40], [150, 40], 6, 2, 128, 1.0, 1.0),               # G = 3 (one head per wave)
+    (987, [210, 90, 300], [210, 1, 1], 8, 2, 64, 1.0, 1.0),         # d = 64, both kinds
+    (988, [129, 512], [129, 1], 16, 2, 128, 0.09, 1.0),             # near-uniform attention
+    (989, [40, 0, 25], [40, 0, 25], 8, 2, 64, 1.0, 1.0),            # an empty sequence in the middle, d = 64
+]
+
+
+@pytest.mark.parametrize("seed,lens,qlens,Hq,Hkv,d,kstd,vstd", CHUNK_CASES)
+def test_fp8_cache_query_chunks_and_mixed_batches(seed, lens, qlens, Hq, Hkv, d, kstd, vstd):
+    from helpers import valid_rows
+    b = W.random_batch(seed, lens, qlens, Hq, Hkv, d, torch.bfloat16, num_probe_heads=min(5, Hq), max_sel_q=3,
+                       max_spans=3)
+    b8 = W.fp8_cache_variant(b, seed + 50, k_std=kstd, v_std=vstd)
+    bd = b8.to(DEV)
+    out = torch.full_like(bd.q, float("nan"))
+    mass = torch.full((b.num_seqs, b.num_probe_heads, b.max_sel_q, b.max_spans), float("nan"), dtype=torch.float32,
+                      device=DEV)
+    call = binding.call_from_batch(bd, out=out, mass=mass)
+    call.launch()
+    torch.cuda.synchronize()
+    assert call.device_status() == 0
+    written = torch.isfinite(out.float()).all(dim=2).all(dim=1).cpu()
+    assert bool((written == valid_rows(b8)).all())
+    res = compare_with_oracle(b8, out, mass, label=f"kv8_chunks_{seed}")
+    print(res, flush=True)
+
+
+def test_fp8_cache_c2_shape_shrunk():
+    """The 8B prefill geometry over an 8-bit cache, eight times shorter, every row against the oracle."""
+    b = W.c2_prefill_8b(device="cpu", peaked=True, shrink=8)
+    b8 = W.fp8_cache_variant(b, 990, k_std=1.0, v_std=1.0)
+    bd = b8.to(DEV)
+    call = binding.call_from_batch(bd, batch_kind=binding.BATCH_PREFILL_ONLY)
+    call.out.fill_(float("nan"))
+    call.launch()
+    torch.cuda.synchronize()
+    assert call.device_status() == 0
+    print(compare_with_oracle(b8, call.out, call.mass, label="c2_kv8_shrunk"), flush=True)
+
+
+def test_fp8_cache_chunk_call_writes_its_new_rows_quantised():
+    """k_new / v_new with an 8-bit cache and query chunks: the planning launch quantises the rows into
+    the cache, the chunk kernel then reads them back."""
+    from oracle.capture import kv_write
+    b = W.random_batch(995, [300, 64], [100, 64], 8, 2, 128, torch.bfloat16, num_probe_heads=3, max_sel_q=2,
+                       poison=False)
+    b8 = W.fp8_cache_variant(b, 996, k_std=1.0, v_std=0.5)
+    gen = torch.Generator().manual_seed(997)
+    k_new = torch.randn((b.total_q, 2, 128), generator=gen).to(torch.bfloat16)
+    v_new = (torch.randn((b.total_q, 2, 128), generator=gen) * 0.5).to(torch.bfloat16)
+    want_k, want_v = kv_write(k_new, v_new, b8.block_table, b8.seq_lens, b8.cu_q_lens, b8.k_cache, b8.v_cache,
+                              b8.k_scale, b8.v_scale)
+    after = b8.to("cpu")
+    kw = dict(after.__dict__)
+    kw.update(k_cache=want_k, v_cache=want_v)
+    after = type(after)(**kw)
+    bd = b8.to(DEV)
+    call = binding.call_from_batch(bd, k_new=k_new.to(DEV), v_new=v_new.to(DEV))
+    call.launch()
+    torch.cuda.synchronize()
+    assert torch.equal(bd.k_cache.cpu(), want_k) and torch.equal(bd.v_cache.cpu(), want_v)
+    print(compare_with_oracle(after, call.out, call.mass, label="kv8_chunks_in_call_write"), flush=True)
