@@ -332,7 +332,8 @@ hook_status hook_residual_add_steer(void* hidden, const void* delta, const void*
  *       for j in [0, L_i): the keys of the chosen kv heads, sequences back to back.
  * All arrays are DEVICE pointers, caller-owned; cu_k_lens holds the prefix sums of seq_lens
  * (cu_k_lens[num_seqs] = total_k, which the host needs anyway to size k_out).  Pure data
- * movement: outputs are bit-identical to the inputs they copy.  Asynchronous on `stream`.
+ * movement: outputs are bit-identical to the inputs they copy (the keys of an 8-bit cache as its
+ * bytes, see kv_dtype).  Asynchronous on `stream`.
  * Block ids outside [0, num_blocks) are clamped as in hook_attn_probe.
  */
 typedef struct hook_capture_qk_args {
@@ -354,6 +355,9 @@ typedef struct hook_capture_qk_args {
   void* q_out;                      /* [num_seqs, P, NQ, d] */
   void* k_out;                      /* [total_k, KH, d] */
   void* stream;
+  int32_t kv_dtype;                 /* hook_kv_dtype of k_cache; with HOOK_KV_FP8_E4M3 k_out holds the
+                                       cache's bytes as they are ([total_k, KH, d] bytes; the caller has
+                                       the scales) */
 } hook_capture_qk_args;
 
 hook_status hook_capture_qk(const hook_capture_qk_args* args);

@@ -23,7 +23,7 @@ def capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_se
     for L in lens:
         cu_k.append(cu_k[-1] + L)
     q_out = torch.zeros((num_seqs, len(heads), max_sel_q, d), dtype=q.dtype)
-    k_out = torch.zeros((cu_k[-1], len(kvh), d), dtype=q.dtype)
+    k_out = torch.zeros((cu_k[-1], len(kvh), d), dtype=k_cache.dtype)   # the cache's elements as they are (bytes of an 8-bit cache)
     for i in range(num_seqs):
         n = cu[i + 1] - cu[i]
         for p, h in enumerate(heads):

@@ -55,6 +55,7 @@ class HookCaptureQkArgs(ctypes.Structure):
         ("num_capture_kv_heads", ctypes.c_int32), ("capture_kv_heads", ctypes.c_void_p),
         ("cu_k_lens", ctypes.c_void_p), ("total_k", ctypes.c_int32),
         ("q_out", ctypes.c_void_p), ("k_out", ctypes.c_void_p), ("stream", ctypes.c_void_p),
+        ("kv_dtype", ctypes.c_int32),
     ]
 
 
@@ -360,7 +361,7 @@ def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, m
     if q_out is None:
         q_out = torch.empty((num_seqs, P, int(max_sel_q), d), dtype=q.dtype, device=q.device)
     if k_out is None:
-        k_out = torch.empty((int(total_k), KH, d), dtype=q.dtype, device=q.device)
+        k_out = torch.empty((int(total_k), KH, d), dtype=k_cache.dtype, device=q.device)   # bytes for an 8-bit cache
     a = HookCaptureQkArgs()
     a.num_seqs, a.total_q, a.num_q_heads, a.num_kv_heads = num_seqs, total_q, Hq, Hkv
     a.head_dim, a.block_size, a.max_blocks_per_seq, a.num_blocks = d, B, max_blocks, num_blocks
@@ -371,6 +372,7 @@ def hook_capture_qk(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, m
     a.num_capture_kv_heads, a.capture_kv_heads = KH, _p(capture_kv_heads)
     a.cu_k_lens, a.total_k = _p(cu_k_lens), int(total_k)
     a.q_out, a.k_out, a.stream = _p(q_out), _p(k_out), _stream_handle(stream)
+    a.kv_dtype = KV_FP8_E4M3 if k_cache.dtype == torch.uint8 else KV_SAME
     st = lib.hook_capture_qk(ctypes.byref(a))
     if st != HOOK_OK:
         raise HookError(st, "hook_capture_qk")

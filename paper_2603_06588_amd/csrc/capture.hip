@@ -8,7 +8,9 @@ namespace hook {
 namespace {
 
 struct CaptureParams {
-  int num_seqs, total_q, Hq, Hkv, max_blocks, num_blocks, row_chunks;  // row_chunks = d * esize / 16
+  int num_seqs, total_q, Hq, Hkv, max_blocks, num_blocks;
+  int row_chunks;     // 16-byte chunks per query row: d * esize / 16
+  int k_row_chunks;   // 16-byte chunks per key row (fewer with an 8-bit cache)
   const uint4* q;
   const uint4* k_cache;
   const int* block_table;
@@ -35,7 +37,7 @@ constexpr int kInFlight = 8;
 
 __global__ __launch_bounds__(256) void k_capture_k(const CaptureParams p) {
   __shared__ long long src_row[kTokTile];   // (blk * Hkv) * kBlock + slot, or -1 for a zero row
-  const int rc = p.row_chunks;
+  const int rc = p.k_row_chunks;
   const int tok0 = blockIdx.x * kTokTile;
   if (threadIdx.x < kTokTile) {
     const int tok = tok0 + threadIdx.x;
@@ -118,12 +120,16 @@ extern "C" hook_status hook_capture_qk(const hook_capture_qk_args* a) {
   if (a->dtype != HOOK_BF16 && a->dtype != HOOK_F32) return HOOK_ERR_UNSUPPORTED;
   const int esize = a->dtype == HOOK_BF16 ? 2 : 4;
   if ((a->head_dim * esize) % 16 != 0) return HOOK_ERR_UNSUPPORTED;
+  if (a->kv_dtype != HOOK_KV_SAME && a->kv_dtype != HOOK_KV_FP8_E4M3) return HOOK_ERR_SHAPE;
+  const int kesize = a->kv_dtype == HOOK_KV_FP8_E4M3 ? 1 : esize;
+  if (a->kv_dtype == HOOK_KV_FP8_E4M3 && (a->dtype != HOOK_BF16 || a->head_dim % 16 != 0)) return HOOK_ERR_UNSUPPORTED;
   if (a->num_probe_heads > 0 && (a->max_sel_q < 1 || a->max_sel_q > HOOK_MAX_SEL_Q)) return HOOK_ERR_SHAPE;
   if (a->num_seqs == 0) return HOOK_OK;
   CaptureParams p{};
   p.num_seqs = a->num_seqs; p.total_q = a->total_q; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads;
   p.max_blocks = a->max_blocks_per_seq; p.num_blocks = a->num_blocks;
   p.row_chunks = a->head_dim * esize / 16;
+  p.k_row_chunks = a->head_dim * kesize / 16;
   p.q = static_cast<const uint4*>(a->q); p.k_cache = static_cast<const uint4*>(a->k_cache);
   p.block_table = a->block_table; p.seq_lens = a->seq_lens; p.cu_q_lens = a->cu_q_lens;
   p.P = a->num_probe_heads; p.probe_heads = a->probe_heads; p.NQ = a->max_sel_q; p.query_sel = a->query_sel;

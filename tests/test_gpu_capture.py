@@ -228,3 +228,23 @@ def test_attention_call_writes_the_new_rows_itself(variant):
         live = ~torch.isnan(ref.k_cache.float())
         assert torch.equal(bits(one.k_cache)[live.cpu()], bits(ref.k_cache)[live.cpu()])
         assert torch.equal(torch.isnan(one.k_cache.float()), ~live)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_capture_copies_the_bytes_of_an_8_bit_cache(d):
+    """Keys of an 8-bit cache are gathered as the bytes they are (the caller holds the scales); queries as ever."""
+    from oracle.capture import capture_qk
+    from paper_2603_06588_amd import binding
+    b = W.random_batch(340 + d, [333, 17, 64, 1000, 9], [100, 1, 64, 1, 0], 8, 2, d, torch.bfloat16, num_probe_heads=3,
+                       max_sel_q=4)
+    b8 = W.fp8_cache_variant(b, 341)
+    kvh = torch.tensor([1, 0], dtype=torch.int32)
+    ref_q, ref_k, cu_k = capture_qk(b8.q, b8.k_cache, b8.block_table, b8.seq_lens, b8.cu_q_lens, b8.probe_heads,
+                                    b8.max_sel_q, b8.query_sel, kvh)
+    assert ref_k.dtype == torch.uint8
+    bd = b8.to(DEV)
+    got_q, got_k = binding.hook_capture_qk(bd.q, bd.k_cache, bd.block_table, bd.seq_lens, bd.cu_q_lens, bd.probe_heads,
+                                           bd.max_sel_q, bd.query_sel, kvh.to(DEV), cu_k.to(DEV), int(cu_k[-1]))
+    torch.cuda.synchronize()
+    assert got_k.dtype == torch.uint8 and torch.equal(got_k.cpu(), ref_k)
+    assert torch.equal(bits(got_q), bits(ref_q))
