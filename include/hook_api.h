@@ -68,7 +68,7 @@ typedef enum { HOOK_BF16 = 0, HOOK_F32 = 1 } hook_dtype;
  * Needs HOOK_BF16 queries; the cache layout stays [num_blocks, Hkv, B, d] with one byte per
  * element.  Any batch is served: single rows stream the bytes as they are (the bandwidth-bound
  * case the format pays for), query chunks widen them to bf16 on their way into local memory, so a
- * chunked prefill can run on the same cache.  hook_span_mass does not take it.  The paper does not
+ * chunked prefill can run on the same cache.  hook_span_mass takes it as well (k_scale).  The paper does not
  * discuss cache precision; this is the usual serving option of halving the bytes a decode step
  * streams.
  */
@@ -410,7 +410,8 @@ hook_status hook_kv_write(const hook_kv_write_args* args);
  *     aligned) the two passes run as two kernels split over keys and spans and use the whole chip;
  *     without it one workgroup per (sequence, head, 16 rows) does everything (same results to
  *     rounding, several times slower on long sequences),
- *   - only HOOK_BF16 inputs are supported (HOOK_ERR_UNSUPPORTED otherwise).
+ *   - only HOOK_BF16 inputs are supported (HOOK_ERR_UNSUPPORTED otherwise); the key cache may be
+ *     8-bit (kv_dtype, k_scale; v_scale is not read),
  * Two passes over the keys of each (sequence, probed head, 16-row block): exact softmax maximum
  * and normaliser first, then the span sums; no atomics, results reproducible bit for bit.
  * A content-free calibration prompt is a second call; hook_reduce_mass with negated weights

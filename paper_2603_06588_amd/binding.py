@@ -262,7 +262,7 @@ def hook_attn_probe(q, k_cache, v_cache, block_table, seq_lens, cu_q_lens, probe
 
 def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, max_sel_q, query_sel, max_spans,
                    key_spans, scale: float = 0.0, mass=None, stream=None, workspace=None,
-                   use_workspace: bool = True) -> torch.Tensor:
+                   use_workspace: bool = True, k_scale=None) -> torch.Tensor:
     """mass [num_seqs, P, NQ, S] for up to HOOK_MAX_SPANS_WIDE spans; computes no attention output.
     A scratch tensor lets the library split the work over the chip; it is allocated here unless
     one is passed in or use_workspace is False."""
@@ -285,6 +285,8 @@ def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, ma
     a.max_sel_q, a.query_sel = int(max_sel_q), _p(query_sel)
     a.max_spans, a.key_spans = int(max_spans), _p(key_spans)
     a.mass, a.stream = _p(mass), _stream_handle(stream)
+    if k_cache.dtype == torch.uint8:          # 8-bit E4M3 bytes with one scale per kv head
+        a.kv_dtype, a.k_scale = KV_FP8_E4M3, _p(k_scale)
     if workspace is None and use_workspace:
         need = int(lib.hook_span_mass_workspace_bytes(ctypes.byref(a)))
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=q.device) if need else None
@@ -298,7 +300,8 @@ def hook_span_mass(q, k_cache, block_table, seq_lens, cu_q_lens, probe_heads, ma
 
 def hook_span_mass_batch(b, stream=None, mass=None, workspace=None, use_workspace: bool = True) -> torch.Tensor:
     return hook_span_mass(b.q, b.k_cache, b.block_table, b.seq_lens, b.cu_q_lens, b.probe_heads, b.max_sel_q,
-                          b.query_sel, b.max_spans, b.key_spans, b.scale, mass, stream, workspace, use_workspace)
+                          b.query_sel, b.max_spans, b.key_spans, b.scale, mass, stream, workspace, use_workspace,
+                          k_scale=getattr(b, "k_scale", None))
 
 
 def hook_attn_probe_batch(b, stream=None, probe: bool = True):

@@ -19,6 +19,7 @@
 // scale and the value scale into the final normalisation of `out`.  This is what serves query chunks
 // over an 8-bit cache for both head dimensions (the direct-to-LDS kernel for head_dim 128 cannot
 // convert on the way).
+#include "fp8_device.h"
 #include "hook_device.h"
 
 namespace hook {
@@ -43,20 +44,6 @@ struct PrefillCfg {
 // score accumulator hands keys to the second MFMA (see the file comment)
 __device__ __forceinline__ int vt_group_pos(int kg) {
   return 16 * (kg >> 2) + 8 * (kg & 1) + 4 * ((kg >> 1) & 1);
-}
-
-// eight E4M3 bytes (two words) -> eight bf16 values
-__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint2 raw) {
-  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.x, 1.0f, false);
-  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.x, 1.0f, true);
-  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.y, 1.0f, false);
-  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw.y, 1.0f, true);
-  uint4 v;
-  __builtin_memcpy(&v.x, &a, 4);
-  __builtin_memcpy(&v.y, &b, 4);
-  __builtin_memcpy(&v.z, &c, 4);
-  __builtin_memcpy(&v.w, &d, 4);
-  return v;
 }
 
 template <int D, bool KV8>

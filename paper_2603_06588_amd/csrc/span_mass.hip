@@ -12,6 +12,7 @@
 // spans may overlap or be empty.  Scores are bf16 x bf16 products accumulated in fp32 on the
 // matrix cores (16x16x32: 16 keys x 16 rows per instruction), exponentials and sums fp32.
 #include "../../include/hook_api.h"
+#include "fp8_device.h"
 #include "hook_device.h"
 
 #include <cmath>
@@ -26,6 +27,7 @@ constexpr int kSmGroup = 2;     // 16-key tiles per pipeline stage
 struct SpanParams {
   int num_seqs, total_q, Hq, Hkv, G, max_blocks, num_blocks;
   float scale_log2;
+  const float* k_scale;   // 8-bit cache: one fp32 scale per kv head, folded into the softmax scale
   const void* q;
   const void* k_cache;
   const int* block_table;
@@ -53,13 +55,20 @@ struct Frag {
 // K rows of 16 keys as the A operand: lane (key slot l % 16, quarter l / 16) takes the 16-byte
 // chunks 4 s + quarter of its key's row.  `key` is this lane's absolute key (already clamped
 // into the sequence), looked up through the block table.
-template <int D>
+// With an 8-bit cache (KV8) the same eight dimensions are eight bytes, widened to bf16 after the load.
+template <int D, bool KV8>
 __device__ __forceinline__ void load_keys(const SpanParams& p, int blk, int g, int key, int quarter, Frag<D>& f) {
   blk = ((unsigned)blk < (unsigned)p.num_blocks) ? blk : 0;
-  const uint4* row = static_cast<const uint4*>(p.k_cache) +
-                     (((size_t)blk * p.Hkv + g) * kBlock + (key & 15)) * (D / 8);
+  const size_t row_index = ((size_t)blk * p.Hkv + g) * kBlock + (key & 15);
+  if constexpr (KV8) {
+    const uint2* row = static_cast<const uint2*>(p.k_cache) + row_index * (D / 8);
 #pragma unroll
-  for (int s = 0; s < Frag<D>::KSTEPS; ++s) f.k[s] = row[4 * s + quarter];
+    for (int s = 0; s < Frag<D>::KSTEPS; ++s) f.k[s] = e4m3x8_to_bf16x8(row[4 * s + quarter]);
+  } else {
+    const uint4* row = static_cast<const uint4*>(p.k_cache) + row_index * (D / 8);
+#pragma unroll
+    for (int s = 0; s < Frag<D>::KSTEPS; ++s) f.k[s] = row[4 * s + quarter];
+  }
 }
 
 template <int D>
@@ -70,7 +79,7 @@ __device__ __forceinline__ f32x4 scores(const Frag<D>& f, const bf16x8 (&qf)[D /
 // arithmetic on the current group - so neither load latency sits on the critical path.
 // `use(tile_first_key, scores[NB])` is called for every tile whose first key is below `end`; NB blocks
 // of 16 query rows share every K fetch.
-template <int D, int NB, typename F>
+template <int D, int NB, bool KV8, typename F>
 __device__ __forceinline__ void stream_keys(const SpanParams& p, const int* bt, int g, int j, int quarter,
                                             const bf16x8 (&qf)[NB][D / 32], int first, int step, int end, int pos_max,
                                             F&& use) {
@@ -81,7 +90,7 @@ __device__ __forceinline__ void stream_keys(const SpanParams& p, const int* bt, 
   };
   auto rows = [&](int base, const int (&id)[kSmGroup], Frag<D> (&f)[kSmGroup]) {
 #pragma unroll
-    for (int u = 0; u < kSmGroup; ++u) load_keys<D>(p, id[u], g, lane_key(base, u), quarter, f[u]);
+    for (int u = 0; u < kSmGroup; ++u) load_keys<D, KV8>(p, id[u], g, lane_key(base, u), quarter, f[u]);
   };
   auto work = [&](int base, const Frag<D> (&f)[kSmGroup]) {
 #pragma unroll
@@ -128,7 +137,7 @@ __device__ __forceinline__ f32x4 scores(const Frag<D>& f, const bf16x8 (&qf)[D /
   return acc;
 }
 
-template <int D>
+template <int D, bool KV8>
 __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p) {
   __shared__ float sh_m[kSmWaves][kSmRows];
   __shared__ float sh_l[kSmWaves][kSmRows];
@@ -165,12 +174,12 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
 #pragma unroll
     for (int s = 0; s < D / 32; ++s) qf[0][s] = qp[4 * s + quarter];
   }
-  const float c = p.scale_log2;
+  const float c = KV8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
 
   // ---- pass 1: row maximum and normaliser
   float m = -INFINITY, l = 0.0f;
   const int ntile = pos_max / 16 + 1;
-  stream_keys<D, 1>(p, bt, g, j, quarter, qf, 16 * kSmGroup * wave, 16 * kSmGroup * kSmWaves, 16 * ntile, pos_max,
+  stream_keys<D, 1, KV8>(p, bt, g, j, quarter, qf, 16 * kSmGroup * wave, 16 * kSmGroup * kSmWaves, 16 * ntile, pos_max,
                     [&](int key0, const f32x4 (&sc)[1]) {
     const f32x4 s4 = sc[0];
     float sv[4];
@@ -218,7 +227,7 @@ __global__ __launch_bounds__(kSmWaves * 64) void k_span_mass(const SpanParams p)
     const int e = min(p.key_spans[((size_t)i * p.S + r) * 2 + 1], pos_max + 1);
     if (e <= a) continue;                          // uniform; mass was zero-filled
     float acc = 0.0f;
-    stream_keys<D, 1>(p, bt, g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max, [&](int key0, const f32x4 (&sc)[1]) {
+    stream_keys<D, 1, KV8>(p, bt, g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max, [&](int key0, const f32x4 (&sc)[1]) {
       const f32x4 s4 = sc[0];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
@@ -300,7 +309,7 @@ __device__ __forceinline__ bool row_blocks(const SpanParams& p, int i, int ps, i
   return true;
 }
 
-template <int D>
+template <int D, bool KV8>
 __global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParams p) {
   __shared__ float sh_m[kSplitWaves][kSplitBlocks][kSmRows];
   __shared__ float sh_l[kSplitWaves][kSplitBlocks][kSmRows];
@@ -323,14 +332,14 @@ __global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParam
   bf16x8 qf[kSplitBlocks][D / 32];
 #pragma unroll
   for (int nb = 0; nb < kSplitBlocks; ++nb) load_q<D>(p, r[nb], quarter, qf[nb]);
-  const float c = p.scale_log2;
+  const float c = KV8 ? p.scale_log2 * p.k_scale[r[0].g] : p.scale_log2;
   const int ntile = pos_max / 16 + 1;
   const int per = (ntile + p.nsplit - 1) / p.nsplit;           // tiles per split
   const int lo = 16 * per * sp, hi = min(16 * per * (sp + 1), 16 * ntile);
   float m[kSplitBlocks], l[kSplitBlocks];
 #pragma unroll
   for (int nb = 0; nb < kSplitBlocks; ++nb) { m[nb] = -INFINITY; l[nb] = 0.0f; }
-  stream_keys<D, kSplitBlocks>(p, bt, r[0].g, j, quarter, qf, lo + 16 * kSmGroup * wave, 16 * kSmGroup * kSplitWaves,
+  stream_keys<D, kSplitBlocks, KV8>(p, bt, r[0].g, j, quarter, qf, lo + 16 * kSmGroup * wave, 16 * kSmGroup * kSplitWaves,
                                hi, pos_max, [&](int key0, const f32x4 (&sc)[kSplitBlocks]) {
 #pragma unroll
     for (int nb = 0; nb < kSplitBlocks; ++nb) {
@@ -378,7 +387,7 @@ __global__ __launch_bounds__(kSplitWaves * 64) void k_span_stats(const SpanParam
   }
 }
 
-template <int D>
+template <int D, bool KV8>
 __global__ __launch_bounds__(kSplitWaves * 64) void k_span_sums(const SpanParams p) {
   const int i = blockIdx.z / p.sgroups, sg = blockIdx.z % p.sgroups, ps = blockIdx.y;
   const int lane = threadIdx.x & 63;
@@ -392,7 +401,7 @@ __global__ __launch_bounds__(kSplitWaves * 64) void k_span_sums(const SpanParams
   bf16x8 qf[kSplitBlocks][D / 32];
 #pragma unroll
   for (int nb = 0; nb < kSplitBlocks; ++nb) load_q<D>(p, r[nb], quarter, qf[nb]);
-  const float c = p.scale_log2;
+  const float c = KV8 ? p.scale_log2 * p.k_scale[r[0].g] : p.scale_log2;
   // each row's softmax maximum and normaliser from the key splits of the first kernel
   float M[kSplitBlocks], inv[kSplitBlocks];
 #pragma unroll
@@ -419,7 +428,7 @@ __global__ __launch_bounds__(kSplitWaves * 64) void k_span_sums(const SpanParams
     float acc[kSplitBlocks];
 #pragma unroll
     for (int nb = 0; nb < kSplitBlocks; ++nb) acc[nb] = 0.0f;
-    stream_keys<D, kSplitBlocks>(p, bt, r[0].g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max,
+    stream_keys<D, kSplitBlocks, KV8>(p, bt, r[0].g, j, quarter, qf, a, 16 * kSmGroup, e, pos_max,
                                  [&](int key0, const f32x4 (&sc)[kSplitBlocks]) {
 #pragma unroll
       for (int nb = 0; nb < kSplitBlocks; ++nb)
@@ -468,7 +477,6 @@ __global__ __launch_bounds__(256) void k_zero_mass(float* ptr, size_t n) {
 extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   using namespace hook;
   if (!a) return HOOK_ERR_NULL;
-  if (a->kv_dtype != HOOK_KV_SAME) return HOOK_ERR_UNSUPPORTED;   // reads 16-bit keys only
   if (a->num_seqs < 0 || a->total_q < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 ||
       a->max_blocks_per_seq <= 0 || a->num_blocks <= 0 || a->head_dim <= 0)
     return HOOK_ERR_SHAPE;
@@ -483,8 +491,12 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   if (!a->probe_heads || !a->query_sel || !a->key_spans || !a->mass) return HOOK_ERR_NULL;
   if (a->num_seqs == 0) return HOOK_OK;
   if (!a->q || !a->k_cache || !a->block_table || !a->seq_lens || !a->cu_q_lens) return HOOK_ERR_NULL;
+  if (a->kv_dtype != HOOK_KV_SAME && a->kv_dtype != HOOK_KV_FP8_E4M3) return HOOK_ERR_SHAPE;
+  const bool kv8 = a->kv_dtype == HOOK_KV_FP8_E4M3;
+  if (kv8 && !a->k_scale) return HOOK_ERR_NULL;
 
   SpanParams p{};
+  p.k_scale = a->k_scale;
   p.num_seqs = a->num_seqs; p.total_q = a->total_q; p.Hq = a->num_q_heads; p.Hkv = a->num_kv_heads;
   p.G = p.Hq / p.Hkv; p.max_blocks = a->max_blocks_per_seq; p.num_blocks = a->num_blocks;
   const float scale = a->scale > 0.0f ? a->scale : 1.0f / std::sqrt((float)a->head_dim);
@@ -502,12 +514,19 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
     p.nsplit = geo.nsplit; p.sgroups = geo.sgroups; p.nq_pad = geo.nq_pad;
     const unsigned gx = (unsigned)((geo.nq_pad / kSmRows + kSplitBlocks - 1) / kSplitBlocks);
     const dim3 ga(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.nsplit)), gb(gx, (unsigned)P, (unsigned)(p.num_seqs * geo.sgroups));
-    if (a->head_dim == 128) {
-      hipLaunchKernelGGL(k_span_stats<128>, ga, dim3(kSplitWaves * 64), 0, st, p);
-      hipLaunchKernelGGL(k_span_sums<128>, gb, dim3(kSplitWaves * 64), 0, st, p);
+    const dim3 tb(kSplitWaves * 64);
+    if (a->head_dim == 128 && !kv8) {
+      hipLaunchKernelGGL((k_span_stats<128, false>), ga, tb, 0, st, p);
+      hipLaunchKernelGGL((k_span_sums<128, false>), gb, tb, 0, st, p);
+    } else if (a->head_dim == 128) {
+      hipLaunchKernelGGL((k_span_stats<128, true>), ga, tb, 0, st, p);
+      hipLaunchKernelGGL((k_span_sums<128, true>), gb, tb, 0, st, p);
+    } else if (!kv8) {
+      hipLaunchKernelGGL((k_span_stats<64, false>), ga, tb, 0, st, p);
+      hipLaunchKernelGGL((k_span_sums<64, false>), gb, tb, 0, st, p);
     } else {
-      hipLaunchKernelGGL(k_span_stats<64>, ga, dim3(kSplitWaves * 64), 0, st, p);
-      hipLaunchKernelGGL(k_span_sums<64>, gb, dim3(kSplitWaves * 64), 0, st, p);
+      hipLaunchKernelGGL((k_span_stats<64, true>), ga, tb, 0, st, p);
+      hipLaunchKernelGGL((k_span_sums<64, true>), gb, tb, 0, st, p);
     }
     return hipGetLastError() == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
   }
@@ -518,8 +537,11 @@ extern "C" hook_status hook_span_mass(const hook_attn_probe_args* a) {
   hipLaunchKernelGGL(k_zero_mass, dim3((unsigned)zb), dim3(256), 0, st, p.mass, nmass);
   if (hipGetLastError() != hipSuccess) return HOOK_ERR_LAUNCH;
   const dim3 grid((unsigned)((p.NQ + kSmRows - 1) / kSmRows), (unsigned)P, (unsigned)p.num_seqs);
-  if (a->head_dim == 128) hipLaunchKernelGGL(k_span_mass<128>, grid, dim3(kSmWaves * 64), 0, st, p);
-  else hipLaunchKernelGGL(k_span_mass<64>, grid, dim3(kSmWaves * 64), 0, st, p);
+  const dim3 tb(kSmWaves * 64);
+  if (a->head_dim == 128 && !kv8) hipLaunchKernelGGL((k_span_mass<128, false>), grid, tb, 0, st, p);
+  else if (a->head_dim == 128) hipLaunchKernelGGL((k_span_mass<128, true>), grid, tb, 0, st, p);
+  else if (!kv8) hipLaunchKernelGGL((k_span_mass<64, false>), grid, tb, 0, st, p);
+  else hipLaunchKernelGGL((k_span_mass<64, true>), grid, tb, 0, st, p);
   return hipGetLastError() == hipSuccess ? HOOK_OK : HOOK_ERR_LAUNCH;
 }
 

@@ -112,3 +112,24 @@ def test_span_mass_with_invalid_device_contents_completes():
     assert (got[0] - want[0]).abs().max() <= MASS_TOL
     assert (got[2] == 0).all()
     assert abs(float(got[1, 0, 0, 0]) - 1.0) <= MASS_TOL and float(got[1, 0, 0, 1]) == 0.0
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_span_mass_over_an_8_bit_cache(d):
+    """The same pass over E4M3 key bytes with one scale per kv head: both forms against the oracle, which
+    dequantises every byte; and the attention call's own probe on the same batch agrees."""
+    from paper_2603_06588_amd import binding
+    lens, qlens = [333, 90, 64, 1000, 17], [333, 1, 0, 40, 17]
+    b = W.random_batch(560 + d, lens, qlens, 8, 2, d, torch.bfloat16, std=1.0, num_probe_heads=3, max_sel_q=37,
+                       max_spans=40)
+    b8 = W.fp8_cache_variant(b, 561, k_std=1.0, v_std=1.0)
+    got, want = _check(b8)
+    assert want.abs().max() > 0.05
+    few = W.random_batch(570 + d, [300, 150, 700], [45, 150, 1], 8, 2, d, torch.bfloat16, num_probe_heads=4, max_sel_q=5,
+                         max_spans=6)
+    few8 = W.fp8_cache_variant(few, 571).to(DEV)
+    call = binding.call_from_batch(few8)
+    call.launch()
+    wide = binding.hook_span_mass_batch(few8)
+    torch.cuda.synchronize()
+    assert (call.mass - wide).abs().max().item() <= 2e-5
